@@ -1,0 +1,199 @@
+"""ctypes front end of the CPU oracle (``lp_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's CPU-baseline leg.  The HIP library and its Python binding never
+import this module, and this module imports nothing from them.
+
+The functions mirror the C ones one to one; numpy is used for buffers only, no
+arithmetic of the method happens on this side.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lp_oracle.c")
+_LIB = os.path.join(_HERE, "liblp_oracle.so")
+
+# -ffp-contract=off and no -ffast-math: the reconstruction's binary32 operation
+# order is part of the definition being checked.
+_CFLAGS = ["-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile lp_oracle.c with gcc into liblp_oracle.so (next to the source)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(["gcc", *_CFLAGS, "-o", tmp, _SRC, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Part(C.Structure):
+    _fields_ = [
+        ("alpha", C.c_int32), ("beta", C.c_int32),
+        ("alpha_ext", C.c_int32), ("beta_ext", C.c_int32),
+        ("s", C.c_int32), ("e", C.c_int32), ("len", C.c_int32),
+        ("delta_start", C.c_int32), ("delta_end", C.c_int32),
+        ("shape", C.c_int32 * 4),
+        ("elem_offset", C.c_int64), ("n_elems", C.c_int64), ("n_tokens", C.c_int64),
+    ]
+
+
+@dataclass(frozen=True)
+class Part:
+    alpha: int
+    beta: int
+    alpha_ext: int
+    beta_ext: int
+    s: int
+    e: int
+    len: int
+    delta_start: int
+    delta_end: int
+    shape: tuple
+    elem_offset: int
+    n_elems: int
+    n_tokens: int
+
+
+@dataclass(frozen=True)
+class Plan:
+    latent: tuple          # (C, T, H, W)
+    patch: tuple           # (pT, pH, pW)
+    K: int
+    dim: int               # 0 = T, 1 = H, 2 = W
+    parts: tuple           # of Part
+    total_elems: int
+
+    def _c_parts(self):
+        arr = (_Part * self.K)()
+        for i, p in enumerate(self.parts):
+            a = arr[i]
+            a.alpha, a.beta, a.alpha_ext, a.beta_ext = p.alpha, p.beta, p.alpha_ext, p.beta_ext
+            a.s, a.e, a.len, a.delta_start, a.delta_end = p.s, p.e, p.len, p.delta_start, p.delta_end
+            for d in range(4):
+                a.shape[d] = p.shape[d]
+            a.elem_offset, a.n_elems, a.n_tokens = p.elem_offset, p.n_elems, p.n_tokens
+        return arr
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i32p = C.POINTER(C.c_int32)
+        lib.lpo_rotation_dim.argtypes = [C.c_int64]
+        lib.lpo_rotation_dim.restype = C.c_int
+        lib.lpo_plan.argtypes = [i32p, i32p, C.c_int32, C.c_int32, C.c_double, C.c_int32, C.POINTER(_Part)]
+        lib.lpo_plan.restype = C.c_int
+        lib.lpo_weight.argtypes = [C.c_int32] * 4
+        lib.lpo_weight.restype = C.c_float
+        lib.lpo_partition.argtypes = [i32p, C.c_int32, C.c_int32, C.POINTER(_Part), C.c_void_p, C.c_void_p]
+        lib.lpo_partition.restype = None
+        lib.lpo_reconstruct.argtypes = [i32p, C.c_int32, C.c_int32, C.POINTER(_Part), C.c_void_p, C.c_void_p]
+        lib.lpo_reconstruct.restype = None
+        lib.lpo_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                      C.c_int32, C.c_int64, C.c_int64, C.c_double, C.c_void_p, C.c_int64]
+        lib.lpo_attention.restype = C.c_int
+        lib.lpo_num_threads.argtypes = []
+        lib.lpo_num_threads.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _i32(vals):
+    return (C.c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def rotation_dim(step_1based: int) -> int:
+    """Eq. 3: 0 = temporal, 1 = height, 2 = width for the 1-based step index."""
+    d = _load().lpo_rotation_dim(int(step_1based))
+    if d < 0:
+        raise ValueError("step index must be >= 1")
+    return d
+
+
+def plan(latent: Sequence[int], patch: Sequence[int], K: int, dim: int, *,
+         overlap_patches: int = -1, r: float = 0.0) -> Plan:
+    """Eq. 7-9, 11: the K partitions of a [C,T,H,W] latent along ``dim``."""
+    if K < 1:
+        raise ValueError("K must be >= 1")
+    parts = (_Part * K)()
+    rc = _load().lpo_plan(_i32(latent), _i32(patch), K, int(overlap_patches), float(r), int(dim), parts)
+    if rc != 0:
+        raise ValueError("arguments outside what the method defines")
+    out: List[Part] = []
+    for a in parts:
+        out.append(Part(a.alpha, a.beta, a.alpha_ext, a.beta_ext, a.s, a.e, a.len, a.delta_start,
+                        a.delta_end, tuple(a.shape), a.elem_offset, a.n_elems, a.n_tokens))
+    total = sum(p.n_elems for p in out)
+    return Plan(tuple(int(v) for v in latent), tuple(int(v) for v in patch), K, int(dim), tuple(out), total)
+
+
+def weight(j: int, length: int, delta_start: int, delta_end: int) -> np.float32:
+    """Eq. 12 at local position j (binary32)."""
+    return np.float32(_load().lpo_weight(j, length, delta_start, delta_end))
+
+
+def partition(pl: Plan, z: np.ndarray) -> np.ndarray:
+    """Eq. 10: packed sub-latents (float32, total_elems) of latent z [C,T,H,W]."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    assert z.shape == pl.latent
+    subs = np.empty(pl.total_elems, dtype=np.float32)
+    _load().lpo_partition(_i32(pl.latent), pl.dim, pl.K, pl._c_parts(), z.ctypes.data, subs.ctypes.data)
+    return subs
+
+
+def reconstruct(pl: Plan, preds: np.ndarray) -> np.ndarray:
+    """Eq. 13-17: stitched [C,T,H,W] float32 latent from packed predictions."""
+    preds = np.ascontiguousarray(preds, dtype=np.float32)
+    assert preds.shape == (pl.total_elems,)
+    out = np.empty(pl.latent, dtype=np.float32)
+    _load().lpo_reconstruct(_i32(pl.latent), pl.dim, pl.K, pl._c_parts(), preds.ctypes.data, out.ctypes.data)
+    return out
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, *, scale: Optional[float] = None,
+              rows: Optional[Sequence[int]] = None) -> np.ndarray:
+    """softmax(scale q k^T) v per head.
+
+    q, k, v: uint16 arrays of bf16 bit patterns, shape [n, heads, head_dim],
+    C-contiguous.  ``rows`` selects query rows (each still sees all n keys).
+    Returns float32 [n_rows, heads, head_dim].
+    """
+    for a in (q, k, v):
+        assert a.dtype == np.uint16 and a.ndim == 3 and a.flags.c_contiguous
+    assert q.shape == k.shape == v.shape
+    n, heads, hd = q.shape
+    if scale is None:
+        scale = 1.0 / float(np.sqrt(np.float64(hd)))
+    if rows is None:
+        rows_arr, n_rows, rows_ptr = None, n, None
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        assert rows_arr.ndim == 1
+        if rows_arr.size and (rows_arr.min() < 0 or rows_arr.max() >= n):
+            raise IndexError("query row out of range")
+        n_rows, rows_ptr = rows_arr.size, rows_arr.ctypes.data
+    out = np.zeros((n_rows, heads, hd), dtype=np.float32)
+    rc = _load().lpo_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, out.ctypes.data, n, heads, hd,
+                               heads * hd, hd, float(scale), rows_ptr, n_rows)
+    if rc != 0:
+        raise MemoryError("oracle attention could not allocate its work buffers")
+    return out
+
+
+def num_threads() -> int:
+    """Threads the oracle's parallel loops use."""
+    return int(_load().lpo_num_threads())

@@ -1,0 +1,98 @@
+"""Seeded synthetic inputs for the LP hot path.
+
+Holds shapes, seeds and random draws only -- none of the method's arithmetic.
+Both the HIP path (through the binding) and the CPU oracle are fed from here so
+that they see identical bits; neither side is imported by this module.
+
+Workload shapes follow the WAN-style latent layout [16, 1 + (F - 1) / 4, H/8, W/8]
+with patch (1, 2, 2) (the 480p case is 60 x 104, which is what the paper's
+communication table implies for its 49- and 81-frame runs).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+DIM_NAMES = ("T", "H", "W")
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    latent: Tuple[int, int, int, int]      # C, T, H, W
+    patch: Tuple[int, int, int]            # pT, pH, pW
+    K: int
+    overlap_patches: int
+    dims: Tuple[int, ...]                  # partition dims visited, in order (0=T,1=H,2=W)
+    heads: int
+    head_dim: int
+    layers: int = 1
+
+
+# The five benchmark configurations (index = position in the baseline's list).
+WORKLOADS = (
+    Workload("tiny", (16, 5, 16, 16), (1, 2, 2), 2, 1, (2,), 4, 64),
+    Workload("wan1.3b-33f-480p", (16, 9, 60, 104), (1, 2, 2), 4, 1, (0, 1, 2), 12, 128),
+    Workload("wan1.3b-81f-480p", (16, 21, 60, 104), (1, 2, 2), 4, 2, (1,), 12, 128),
+    Workload("dit14b-81f-720p", (16, 21, 90, 160), (1, 2, 2), 8, 2, (2,), 40, 128),
+    Workload("wan1.3b-81f-480p-loop", (16, 21, 60, 104), (1, 2, 2), 4, 2, (0, 1, 2), 12, 128, layers=30),
+)
+
+
+def seed_for(cfg: int, dim: int, k: int, tensor: int = 0) -> int:
+    """One stream per (config, partition dim, partition, tensor id)."""
+    return 0x4C500000 + 0x1000 * tensor + 0x100 * cfg + 0x10 * dim + k
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round binary32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return rounded.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns to binary32 (exact)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def normal_f32(seed: int, shape: Sequence[int]) -> np.ndarray:
+    """N(0,1) binary32 tensor from a fixed stream."""
+    rng = np.random.Generator(np.random.Philox(seed))
+    return rng.standard_normal(size=tuple(shape), dtype=np.float32)
+
+
+def latent(seed: int, shape: Sequence[int]) -> np.ndarray:
+    return normal_f32(seed, shape)
+
+
+def index_coded(shape: Sequence[int]) -> np.ndarray:
+    """Latent whose value at linear index i is float(i mod 2^20): any mis-indexing shows."""
+    n = int(np.prod(shape))
+    return (np.arange(n, dtype=np.int64) % (1 << 20)).astype(np.float32).reshape(tuple(shape))
+
+
+def qkv_bf16(seed: int, n_tokens: int, heads: int, head_dim: int):
+    """Q, K, V ~ N(0,1) rounded to bf16, each uint16 [n_tokens, heads, head_dim]."""
+    out = []
+    for t in range(3):
+        x = normal_f32(seed + 0x1000 * (t + 1), (n_tokens, heads, head_dim))
+        out.append(f32_to_bf16_bits(x))
+    return tuple(out)
+
+
+def sample_rows(n: int, count: int, seed: int, tile: int = 64) -> np.ndarray:
+    """Query rows for sampled checks: first, last, rows on both sides of tile
+    edges near the start and the end, then seeded random rows; sorted, unique."""
+    picks = {0, n - 1}
+    for edge in (tile, 2 * tile, 4 * tile, (n // tile) * tile, ((n // tile) - 1) * tile,
+                 (n // (4 * tile)) * 4 * tile):
+        for r in (edge - 1, edge, edge + 1):
+            if 0 <= r < n:
+                picks.add(r)
+    rng = np.random.Generator(np.random.Philox(seed))
+    while len(picks) < min(count, n):
+        picks.add(int(rng.integers(0, n)))
+    return np.array(sorted(picks), dtype=np.int64)
