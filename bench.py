@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the LP hot path on one MI355X.
+
+One "step" = one LP denoising step over one latent: lp_partition of the global
+latent along the step's rotating dimension, lp_attention over every sub-latent
+(the K partitions in turn on this one GPU, `layers` attention calls each), then
+lp_reconstruct of the K predictions.  All inputs are synthetic, seeded, and
+resident in device memory before the timed region starts.
+
+Prints ONE JSON line.  `value` is attention TFLOP/s of the whole step stream
+(attention flops / wall time of the timed steps, partition and reconstruct time
+included).  `roofline` describes the attention kernel (its flops over its own
+HIP-event time inside the timed region), `latent_ops` the two HBM-bound kernels,
+`cpu_baseline` the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+METRIC = "lp_attention TFLOP/s (% bf16 MFMA peak); partition+stitch GB/s (% HBM)"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--workload", type=int, default=1, help="index into the benchmark configurations (default 1)")
+    ap.add_argument("--layers", type=int, default=0, help="attention calls per partition per step (0 = the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default="", help="file with measured HBM bytes per attention launch (optional)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 (got %d). "
+              "No multi-GPU figure exists." % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2512_07350_amd import binding as lp
+    from paper_2512_07350_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream().cuda_stream
+    cfg = args.workload
+    w = synth.WORKLOADS[cfg]
+    layers = args.layers or w.layers
+
+    # ---- plans and device-resident inputs for every partition dim the workload visits
+    z = torch.from_numpy(synth.latent(synth.seed_for(cfg, 0, 0, tensor=9), w.latent)).cuda()
+    out = torch.empty_like(z)
+    state = {}
+    for dim in sorted(set(w.dims)):
+        plan = lp.lp_plan_create(w.latent, w.patch, w.K, dim, overlap_patches=w.overlap_patches)
+        parts = plan.parts()
+        subs = torch.empty(plan.total_elems, dtype=torch.float32, device="cuda")
+        preds = torch.from_numpy(synth.normal_f32(synth.seed_for(cfg, dim, 0, tensor=10), (plan.total_elems,))).cuda()
+        qkv = []
+        for kp, part in enumerate(parts):
+            n = part.n_tokens
+            if n == 0:
+                qkv.append(None)
+                continue
+            host = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
+            dev = [torch.from_numpy(a.view(np.int16)).cuda() for a in host]
+            qkv.append((n, dev[0], dev[1], dev[2], torch.empty_like(dev[0])))
+        state[dim] = dict(plan=plan, parts=parts, subs=subs, preds=preds, qkv=qkv)
+    torch.cuda.synchronize()
+
+    def flops_of(n):
+        return 4.0 * n * n * w.head_dim * w.heads
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def run_step(step_1based, rec=None):
+        dim = w.dims[(step_1based - 1) % len(w.dims)]
+        if len(w.dims) == 3:
+            assert dim == lp.lp_rotation_dim(step_1based)
+        st = state[dim]
+        e0 = ev(); e0.record()
+        lp.lp_partition(st["plan"], z, st["subs"], stream)
+        e1 = ev(); e1.record()
+        att = []
+        for item in st["qkv"]:
+            if item is None:
+                continue
+            n, qd, kd, vd, od = item
+            for _ in range(layers):
+                a0 = ev(); a0.record()
+                lp.lp_attention(qd, kd, vd, od, n, w.heads, w.head_dim, w.heads * w.head_dim, w.head_dim, 0.0, stream)
+                a1 = ev(); a1.record()
+                att.append((a0, a1, n))
+        e2 = ev(); e2.record()
+        lp.lp_reconstruct(st["plan"], st["preds"], out, stream)
+        e3 = ev(); e3.record()
+        if rec is not None:
+            rec.append((dim, e0, e1, att, e2, e3))
+
+    for i in range(args.warmup):
+        run_step(i + 1)
+    torch.cuda.synchronize()
+    records = []
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        run_step(args.warmup + i + 1, records)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    att_ms = att_flops = 0.0
+    att_launches = 0
+    part_ms = rec_ms = part_bytes = rec_bytes = 0.0
+    per_dim = {}
+    for dim, e0, e1, att, e2, e3 in records:
+        st = state[dim]
+        part_ms += e0.elapsed_time(e1)
+        rec_ms += e2.elapsed_time(e3)
+        s_ext = 4.0 * st["plan"].total_elems
+        s_z = 4.0 * st["plan"].latent_elems
+        part_bytes += 2.0 * s_ext              # read each selected element once, write it once
+        rec_bytes += s_ext + s_z               # read every prediction once, write the latent once
+        d = per_dim.setdefault(synth.DIM_NAMES[dim], dict(ms=0.0, flops=0.0, launches=0))
+        for a0, a1, n in att:
+            t = a0.elapsed_time(a1)
+            att_ms += t
+            att_flops += flops_of(n)
+            att_launches += 1
+            d["ms"] += t; d["flops"] += flops_of(n); d["launches"] += 1
+
+    ms_per_step = wall * 1e3 / args.steps
+    value = att_flops / wall / 1e12
+    achieved = att_flops / (att_ms * 1e-3) / 1e12
+    traffic = None
+    if args.traffic_json and os.path.exists(args.traffic_json):
+        traffic = json.load(open(args.traffic_json)).get("attention_bytes_per_launch")
+
+    result = {
+        "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "index": cfg, "latent": list(w.latent), "patch": list(w.patch), "K": w.K,
+                   "overlap_patches": w.overlap_patches, "dims": [synth.DIM_NAMES[d] for d in w.dims],
+                   "heads": w.heads, "head_dim": w.head_dim, "attention_layers_per_partition": layers},
+        "roofline": {"kernel": "attention_kernel<%d>" % w.head_dim, "bound": "mfma",
+                     "achieved": round(achieved, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                     "launches": att_launches, "avg_launch_ms": round(att_ms / max(att_launches, 1), 5),
+                     "avg_flops_per_launch": att_flops / max(att_launches, 1),
+                     "per_dim_tflops": {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) for k, v in per_dim.items()}},
+        "latent_ops": {"bound": "hbm", "peak": PEAK_HBM_GBPS, "unit": "GB/s", "cache": "warm (buffers reused every step)",
+                       "partition": {"GBps": round(part_bytes / (part_ms * 1e-3) / 1e9, 1), "avg_us": round(part_ms * 1e3 / args.steps, 2),
+                                     "frac": round(part_bytes / (part_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)},
+                       "reconstruct": {"GBps": round(rec_bytes / (rec_ms * 1e-3) / 1e9, 1), "avg_us": round(rec_ms * 1e3 / args.steps, 2),
+                                       "frac": round(rec_bytes / (rec_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}},
+        "time_split_ms_per_step": {"partition": round(part_ms / args.steps, 5), "attention": round(att_ms / args.steps, 4),
+                                   "reconstruct": round(rec_ms / args.steps, 5)},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, cfg, state, synth, np, torch)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def cpu_baseline(w, cfg, state, synth, np, torch):
+    """Time the CPU oracle, as it stands, on a bounded sample of this workload: the first
+    dim's step with partition and reconstruct in full and attention on every `stride`-th
+    query row of every partition (each row over all keys).  Also compares the GPU's
+    attention output on those rows with the oracle's."""
+    from oracle import lp_oracle as orc
+    dim = w.dims[0]
+    st = state[dim]
+    ref_plan = orc.plan(w.latent, w.patch, w.K, dim, overlap_patches=w.overlap_patches)
+    total_flops = sum(4.0 * p.n_tokens ** 2 * w.head_dim * w.heads for p in ref_plan.parts)
+    budget_flops = 2.0e11                     # about 10-20 s of oracle work on 8-16 cores
+    stride = max(1, int(np.ceil(total_flops / budget_flops)))
+    z_h = synth.latent(synth.seed_for(cfg, 0, 0, tensor=9), w.latent)
+    preds_h = st["preds"].cpu().numpy()
+    t0 = time.perf_counter()
+    subs_ref = orc.partition(ref_plan, z_h)
+    t_part = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    out_ref = orc.reconstruct(ref_plan, preds_h)
+    t_rec = time.perf_counter() - t0
+    t_att = 0.0
+    flops = 0.0
+    max_err = mean_err = 0.0
+    n_cmp = 0
+    for kp, part in enumerate(ref_plan.parts):
+        n = part.n_tokens
+        if n == 0:
+            continue
+        q, k, v = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
+        rows = np.arange(0, n, stride, dtype=np.int64)
+        t0 = time.perf_counter()
+        want = orc.attention(q, k, v, rows=rows)
+        t_att += time.perf_counter() - t0
+        flops += 4.0 * len(rows) * n * w.head_dim * w.heads
+        got_bits = st["qkv"][kp][4].cpu().numpy().view(np.uint16)
+        err = np.abs(synth.bf16_bits_to_f32(got_bits[rows]) - want)
+        max_err = max(max_err, float(err.max()))
+        mean_err += float(err.sum()); n_cmp += err.size
+    parity_latent = bool(np.array_equal(st["subs"].cpu().numpy(), subs_ref))
+    return {"value": round(flops / t_att / 1e12, 5), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "step along %s of %s: attention on every %d-th query row of all %d partitions (all keys, all heads; "
+                      "%.3g of %.3g flop) in %.1f s; partition %.1f ms and reconstruct %.1f ms in full"
+                      % (synth.DIM_NAMES[dim], w.name, stride, w.K, flops, total_flops, t_att, t_part * 1e3, t_rec * 1e3),
+            "partition_GBps": round(2 * 4.0 * ref_plan.total_elems / t_part / 1e9, 2),
+            "reconstruct_GBps": round(4.0 * (ref_plan.total_elems + int(np.prod(w.latent))) / t_rec / 1e9, 2),
+            "gpu_vs_oracle_on_sample": {"attention_max_abs": max_err, "attention_mean_abs": mean_err / max(n_cmp, 1),
+                                        "partition_bit_exact": parity_latent}}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

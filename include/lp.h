@@ -1,0 +1,149 @@
+/*
+ * lp.h -- C ABI of the MI355X (gfx950) hot path of Latent Parallelism (LP).
+ *
+ * LP serves a video diffusion model on K devices by splitting, at every
+ * denoising step, the latent tensor itself: the step's partition dimension
+ * rotates over temporal / height / width (Sec. 3.2, Eq. 3), the latent is cut
+ * into K patch-aligned overlapping sub-latents along it (Sec. 3.3, Eq. 7-10),
+ * each sub-latent is denoised independently (its DiT blocks run global
+ * self-attention over that sub-latent's patch tokens only; supplement, proof
+ * of Theorem 1, step 3), and the K predictions are stitched back with
+ * position-aware weights (Sec. 3.4, Eq. 11-17).
+ *
+ * This library is that per-device work for one GPU: the integer plan (host),
+ * lp_partition, lp_attention and lp_reconstruct (device).  The K sub-latents
+ * that LP places on K devices are processed in turn on the one device.
+ *
+ * Conventions
+ *  - Every call returns an int status: LP_OK (0) or a negative LP_ERR_* code;
+ *    lp_strerror() names it.  Nothing throws across this boundary.
+ *  - "device pointer" = memory the current HIP device can access (hipMalloc);
+ *    "host pointer" = ordinary process memory.  Device pointers are borrowed
+ *    until the work enqueued by the call has finished; the caller owns them.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Device work is enqueued on it and the call returns without waiting.  No
+ *    call here synchronises, allocates or frees device memory.
+ *  - Dimensions: 0 = temporal (T), 1 = height (H), 2 = width (W).
+ *    Partition index k is 0-based here (the paper counts from 1).
+ *  - Latent layout: binary32 [C, T, H, W], contiguous, W fastest.  Sub-latent k
+ *    is [C, T_k, H_k, W_k] contiguous (only the partition dimension differs
+ *    from the latent's); the K sub-latents are packed back to back in k order,
+ *    sub-latent k starting at element lp_part_info.elem_offset.
+ */
+#ifndef LP_H
+#define LP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LP_OK 0
+#define LP_ERR_INVALID_ARG (-1) /* null pointer, bad index, bad stride, K or r out of range */
+#define LP_ERR_SHAPE (-2)       /* extent < 1, patch < 1, or patch does not divide its extent */
+#define LP_ERR_UNSUPPORTED (-3) /* head_dim not in {64, 128}, K above LP_MAX_PARTS, ...       */
+#define LP_ERR_HIP (-4)         /* a HIP call failed; see lp_last_hip_error()                 */
+#define LP_ERR_NOMEM (-5)       /* host allocation failed                                     */
+
+#define LP_MAX_PARTS 64
+
+/* Problem statement of one LP step (Sec. 3.3: latent size, patch sizes, K, r). */
+typedef struct lp_config {
+    int32_t C, T, H, W;       /* latent extents; C is never partitioned                     */
+    int32_t pT, pH, pW;       /* patch sizes (p_T, p_H, p_W); each must divide its extent   */
+    int32_t K;                /* number of partitions, 1 .. LP_MAX_PARTS                    */
+    int32_t overlap_patches;  /* O >= 0 given directly, or -1: O = floor(L * overlap_ratio) */
+    double overlap_ratio;     /* r in [0, K-1] (Sec. 3.3); read only if overlap_patches < 0 */
+} lp_config;
+
+/* Everything Eq. 7-9 and 11 give for one partition, plus its place in the packed buffer. */
+typedef struct lp_part_info {
+    int32_t alpha, beta;         /* core [alpha, beta) in patches, Eq. 7 (beta may exceed N)  */
+    int32_t alpha_ext, beta_ext; /* extended [alpha', beta') in patches, Eq. 8               */
+    int32_t s, e;                /* latent range [s, e) along the partition dim, Eq. 9       */
+    int32_t len;                 /* l_k = e - s; 0 for an empty partition                    */
+    int32_t delta_start;         /* Eq. 11 front ramp length (latent units)                  */
+    int32_t delta_end;           /* Eq. 11 rear ramp length; <= 0 when the core passes N     */
+    int32_t shape[4];            /* C, T_k, H_k, W_k                                          */
+    int64_t elem_offset;         /* first element of sub-latent k in the packed buffer       */
+    int64_t n_elems;             /* C * T_k * H_k * W_k                                       */
+    int64_t n_tokens;            /* patches in the sub-latent = attention sequence length    */
+} lp_part_info;
+
+typedef struct lp_plan lp_plan; /* opaque; host memory owned by the library */
+
+/*
+ * Eq. 3: partition dimension of the step_1based-th forward pass (1, 2, 3 ->
+ * T, H, W, repeating).  Returns 0, 1 or 2; LP_ERR_INVALID_ARG if step < 1.
+ */
+int lp_rotation_dim(int64_t step_1based);
+
+/*
+ * Eq. 7-9, 11: build the plan of K partitions of cfg's latent along `dim`.
+ * Host only; no GPU work.  On success *out holds a plan the caller releases
+ * with lp_plan_destroy.  With N = D/p patches along dim: L = ceil(N/K),
+ * core_k = [k L, k L + L), O = overlap_patches or floor(L r),
+ * extended = [max(0, alpha - O), min(N, beta + O)), latent range = extended * p.
+ * Errors: LP_ERR_INVALID_ARG (null, dim not 0..2, K < 1, r outside [0, K-1],
+ * O > L (K-1)), LP_ERR_SHAPE, LP_ERR_UNSUPPORTED (K > LP_MAX_PARTS),
+ * LP_ERR_NOMEM.
+ */
+int lp_plan_create(const lp_config *cfg, int32_t dim, lp_plan **out);
+void lp_plan_destroy(lp_plan *plan); /* NULL is allowed */
+
+int32_t lp_plan_num_parts(const lp_plan *plan);   /* K, or LP_ERR_INVALID_ARG            */
+int32_t lp_plan_dim(const lp_plan *plan);         /* 0..2, or LP_ERR_INVALID_ARG         */
+int64_t lp_plan_total_elems(const lp_plan *plan); /* floats in the packed buffer (S_ext) */
+int64_t lp_plan_latent_elems(const lp_plan *plan);/* C*T*H*W (S_z)                       */
+/* Fill *out (host pointer) for partition k in [0, K). */
+int lp_plan_query(const lp_plan *plan, int32_t k, lp_part_info *out);
+
+/*
+ * Eq. 10: subs_packed[elem_offset_k + (c, t, h, w)] = z[c, t + s_k [dim=T],
+ * h + s_k [dim=H], w + s_k [dim=W]] for all K partitions, one launch.
+ * z: device, lp_plan_latent_elems floats, read only.  subs_packed: device,
+ * lp_plan_total_elems floats, fully overwritten; must not alias z.
+ * A pure copy: results are bit-identical to the input elements.
+ */
+int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *stream);
+
+/*
+ * Eq. 12-17: out[x] = A(x) / Z(x) with A = sum_k I_k(x) W^(k)_j pred_k[j],
+ * Z = sum_k I_k(x) W^(k)_j, j = x - s_k, weights by Eq. 12 (front ramp
+ * j/Delta_start, 1 on the core, rear ramp (l_k - j)/Delta_end).
+ * preds_packed: device, same packing as lp_partition's output, read only.
+ * out: device, lp_plan_latent_elems floats, fully overwritten.
+ * Arithmetic is binary32 in a fixed order -- k ascending from A = Z = 0,
+ * w by one IEEE division, A += (w * pred) as a rounded product then a rounded
+ * sum, out = A / Z by IEEE division -- so results are reproducible bit for bit.
+ */
+int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, void *stream);
+
+/*
+ * Self-attention inside one sub-latent: for every head h and token i,
+ *   o[i,h,:] = sum_j softmax_j(scale * <q[i,h,:], k[j,h,:]>) v[j,h,:]
+ * over all n_tokens tokens j of the sub-latent (no mask, not causal).
+ * q, k, v, o: device, bfloat16; element (token, head, d) lives at
+ * token * stride_tok + head * stride_head + d (strides in elements, the same
+ * for all four tensors; d contiguous).  Required: head_dim in {64, 128},
+ * stride_head >= head_dim, stride_tok >= heads * ... such that rows do not
+ * overlap, both strides multiples of 8 and all four base pointers 16-byte
+ * aligned (else LP_ERR_INVALID_ARG).  o must not alias q, k or v.
+ * scale <= 0 selects 1/sqrt(head_dim).  n_tokens = 0 is a successful no-op.
+ * Products run on bf16 MFMA with binary32 accumulation; the softmax is
+ * binary32; probabilities are rounded to bf16 before the second product and
+ * the result is rounded to bf16 on store.
+ */
+int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
+                 int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
+                 float scale, void *stream);
+
+const char *lp_strerror(int status); /* static string, never NULL              */
+int lp_last_hip_error(void);         /* hipError_t of the last LP_ERR_HIP (thread local) */
+const char *lp_version(void);        /* "lp-mi355x x.y (gfx950)"               */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LP_H */

@@ -1,0 +1,279 @@
+// lp_partition / lp_reconstruct: the latent-space halves of an LP step as
+// HBM-bound gather and blend kernels for gfx950.
+//
+//   lp_partition    Sec. 3.3, Eq. 10   sub-latent k = z[..., s_k:e_k, ...]
+//   lp_reconstruct  Sec. 3.4, Eq. 12-17   out = A / Z, weights by Eq. 12
+//
+// Both kernels see the latent as [outer, extent, inner] (outer = channels and
+// the dims before the partition dim, inner = the dims after it) and move
+// VEC-float vectors; VEC is the widest of {4, 2, 1} that every run length,
+// every slice start and both base pointers are aligned to.  One thread owns
+// UNROLL vectors; there is no cross-thread communication and every output
+// element has exactly one writer.
+#include <hip/hip_runtime.h>
+
+#include "lp_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// floor(n / d) for 0 <= n < 2^31 as (n * magic) >> shift with a 64-bit product.
+// With l = ceil(log2 d), magic = floor(2^(31+l) / d) + 1 < 2^32 and shift = 31 + l,
+// magic*d = 2^shift + e with 0 < e <= 2^l, so the error term n*e/(d*2^shift) < 1/d.
+struct FastDiv {
+    uint32_t magic;
+    uint32_t shift;
+    uint32_t d;
+};
+
+FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((uint64_t(1) << l) < d) ++l;
+    f.shift = 31 + l;
+    f.magic = uint32_t(((unsigned __int128)1 << f.shift) / d + 1);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv &f) {
+    return uint32_t((uint64_t(n) * f.magic) >> f.shift);
+}
+
+template <int VEC>
+struct VecT;
+template <>
+struct VecT<4> { using type = float4; };
+template <>
+struct VecT<2> { using type = float2; };
+template <>
+struct VecT<1> { using type = float; };
+
+struct PartitionArgs {
+    uint32_t n_vec[LP_MAX_PARTS];     // vectors in sub-latent k
+    uint32_t dst_off[LP_MAX_PARTS];   // first vector of sub-latent k in the packed buffer
+    uint32_t src_off[LP_MAX_PARTS];   // s_k * inner, in vectors
+    FastDiv run[LP_MAX_PARTS];        // len_k * inner, in vectors (contiguous run per outer index)
+    uint32_t src_stride;              // extent * inner, in vectors
+};
+
+// Eq. 10.  grid = (blocks over the largest sub-latent, K).
+template <int VEC, int UNROLL>
+__global__ __launch_bounds__(kThreads) void partition_kernel(const float *__restrict__ z,
+                                                             float *__restrict__ subs,
+                                                             const PartitionArgs a) {
+    using V = typename VecT<VEC>::type;
+    const int k = blockIdx.y;
+    const uint32_t n_vec = a.n_vec[k];
+    const uint32_t base = blockIdx.x * (kThreads * UNROLL) + threadIdx.x;
+    if (blockIdx.x * (kThreads * UNROLL) >= n_vec) return;
+    const FastDiv run = a.run[k];
+    const V *src = reinterpret_cast<const V *>(z) + a.src_off[k];
+    V *dst = reinterpret_cast<V *>(subs) + a.dst_off[k];
+    V val[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t i = base + u * kThreads;
+        if (i < n_vec) {
+            const uint32_t o = fastdiv(i, run);
+            const uint32_t r = i - o * run.d;
+            val[u] = src[uint64_t(o) * a.src_stride + r];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const uint32_t i = base + u * kThreads;
+        if (i < n_vec) dst[i] = val[u];
+    }
+}
+
+struct ReconstructArgs {
+    int32_t s[LP_MAX_PARTS];            // Eq. 9
+    int32_t e[LP_MAX_PARTS];
+    int32_t len[LP_MAX_PARTS];          // l_k
+    int32_t delta_start[LP_MAX_PARTS];  // Eq. 11
+    int32_t delta_end[LP_MAX_PARTS];
+    uint32_t off[LP_MAX_PARTS];         // first vector of prediction k
+    int32_t K;
+    uint32_t n_vec;                     // vectors in the latent
+    uint32_t inner_vec;                 // inner / VEC (X_PER_ELEM = false), else unused
+    FastDiv lat_run;                    // extent * inner, in vectors
+    FastDiv inner_div;                  // inner, in vectors (X_PER_ELEM = false)
+};
+
+// Eq. 12 at local position j; the cases in the order the paper gives them.
+__device__ __forceinline__ float ramp_weight(int32_t j, int32_t len, int32_t ds, int32_t de) {
+    if (j < ds) return __fdiv_rn(float(j), float(ds));
+    if (j < len - de) return 1.0f;
+    return __fdiv_rn(float(len - j), float(de));
+}
+
+// Eq. 13-17.  X_PER_ELEM: the partition dim is the vectorised (fastest) one, so
+// each element of a vector has its own coordinate x and its own weight.
+template <int VEC, bool X_PER_ELEM>
+__global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__restrict__ preds,
+                                                               float *__restrict__ out,
+                                                               const ReconstructArgs a) {
+    using V = typename VecT<VEC>::type;
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= a.n_vec) return;
+    const uint32_t o = fastdiv(i, a.lat_run);
+    const uint32_t rem = i - o * a.lat_run.d;
+    int32_t x0;       // coordinate along the partition dim of element 0 of this vector
+    uint32_t r_in;    // vector offset inside one x-slab
+    if (X_PER_ELEM) {
+        x0 = int32_t(rem) * VEC;
+        r_in = 0;
+    } else {
+        const uint32_t xq = fastdiv(rem, a.inner_div);
+        x0 = int32_t(xq);
+        r_in = rem - xq * a.inner_div.d;
+    }
+    float A[VEC], Z[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) { A[c] = 0.0f; Z[c] = 0.0f; }
+    const V *pv = reinterpret_cast<const V *>(preds);
+    for (int k = 0; k < a.K; ++k) {
+        const int32_t s = a.s[k];
+        if (x0 < s || x0 >= a.e[k]) continue;      // Eq. 14 (a vector never straddles s_k or e_k)
+        const int32_t j0 = x0 - s;                  // Eq. 13
+        const int32_t len = a.len[k], ds = a.delta_start[k], de = a.delta_end[k];
+        uint64_t idx;
+        if (X_PER_ELEM)
+            idx = uint64_t(a.off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) / VEC;
+        else
+            idx = uint64_t(a.off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) * a.inner_vec + r_in;
+        const V p = pv[idx];
+        const float *pf = reinterpret_cast<const float *>(&p);
+        if (X_PER_ELEM) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                const float w = ramp_weight(j0 + c, len, ds, de);
+                A[c] = __fadd_rn(A[c], __fmul_rn(w, pf[c]));   // Eq. 15: rounded product, rounded sum
+                Z[c] = __fadd_rn(Z[c], w);                      // Eq. 16
+            }
+        } else {
+            const float w = ramp_weight(j0, len, ds, de);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                A[c] = __fadd_rn(A[c], __fmul_rn(w, pf[c]));
+                Z[c] = __fadd_rn(Z[c], w);
+            }
+        }
+    }
+    V res;
+    float *rf = reinterpret_cast<float *>(&res);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) rf[c] = (Z[c] == 1.0f) ? A[c] : __fdiv_rn(A[c], Z[c]);   // Eq. 17 (A/1 = A)
+    reinterpret_cast<V *>(out)[i] = res;
+}
+
+bool aligned_to(const void *p, int bytes) { return (reinterpret_cast<uintptr_t>(p) % bytes) == 0; }
+
+// Widest vector usable for this plan and these pointers.  Either the vector lies
+// inside one coordinate of the partition dim (inner is a multiple of it), or the
+// partition dim is the fastest one (inner == 1) and every slice start, slice
+// length and the extent are multiples of it, so no vector straddles a boundary.
+int pick_vec(const lp_plan *pl, const void *a, const void *b) {
+    for (int vec = 4; vec > 1; vec /= 2) {
+        if (!aligned_to(a, 4 * vec) || !aligned_to(b, 4 * vec)) continue;
+        if (pl->inner % vec == 0) return vec;
+        if (pl->inner != 1 || pl->extent % vec != 0) continue;
+        bool ok = true;
+        for (int k = 0; ok && k < pl->K; ++k) ok = pl->part[k].len % vec == 0 && pl->part[k].s % vec == 0;
+        if (ok) return vec;
+    }
+    return 1;
+}
+
+int check_launch(hipError_t err) {
+    if (err != hipSuccess) {
+        lp::set_last_hip_error(int(err));
+        return LP_ERR_HIP;
+    }
+    return LP_OK;
+}
+
+template <int VEC>
+int launch_partition(const lp_plan *pl, const float *z, float *subs, hipStream_t stream) {
+    constexpr int UNROLL = 4;
+    PartitionArgs a;
+    uint32_t max_vec = 0;
+    for (int k = 0; k < pl->K; ++k) {
+        const lp_part_info &q = pl->part[k];
+        a.n_vec[k] = uint32_t(q.n_elems / VEC);
+        a.dst_off[k] = uint32_t(q.elem_offset / VEC);
+        a.src_off[k] = uint32_t(int64_t(q.s) * pl->inner / VEC);
+        const uint32_t run = uint32_t(int64_t(q.len) * pl->inner / VEC);
+        a.run[k] = make_fastdiv(run ? run : 1);
+        if (a.n_vec[k] > max_vec) max_vec = a.n_vec[k];
+    }
+    a.src_stride = uint32_t(int64_t(pl->extent) * pl->inner / VEC);
+    if (max_vec == 0) return LP_OK;
+    const uint32_t per_block = kThreads * UNROLL;
+    dim3 grid((max_vec + per_block - 1) / per_block, pl->K);
+    hipLaunchKernelGGL((partition_kernel<VEC, UNROLL>), grid, dim3(kThreads), 0, stream, z, subs, a);
+    return check_launch(hipGetLastError());
+}
+
+template <int VEC>
+int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, hipStream_t stream) {
+    ReconstructArgs a;
+    a.K = pl->K;
+    for (int k = 0; k < pl->K; ++k) {
+        const lp_part_info &q = pl->part[k];
+        a.s[k] = q.s;
+        a.e[k] = q.e;
+        a.len[k] = q.len;
+        a.delta_start[k] = q.delta_start;
+        a.delta_end[k] = q.delta_end;
+        a.off[k] = uint32_t(q.elem_offset / VEC);
+    }
+    a.n_vec = uint32_t(pl->latent_elems / VEC);
+    a.lat_run = make_fastdiv(uint32_t(int64_t(pl->extent) * pl->inner / VEC));
+    const bool x_per_elem = (pl->inner % VEC) != 0;   // pick_vec allows this only for inner == 1
+    a.inner_vec = x_per_elem ? 1 : uint32_t(pl->inner / VEC);
+    a.inner_div = make_fastdiv(a.inner_vec);
+    dim3 grid((a.n_vec + kThreads - 1) / kThreads);
+    if (x_per_elem)
+        hipLaunchKernelGGL((reconstruct_kernel<VEC, true>), grid, dim3(kThreads), 0, stream, preds, out, a);
+    else
+        hipLaunchKernelGGL((reconstruct_kernel<VEC, false>), grid, dim3(kThreads), 0, stream, preds, out, a);
+    return check_launch(hipGetLastError());
+}
+
+// The kernels index with 32-bit vector counts; 2^31 vectors is far beyond any latent.
+bool fits_32bit(const lp_plan *pl) {
+    return pl->total_elems < (int64_t(1) << 31) && pl->latent_elems < (int64_t(1) << 31);
+}
+
+}  // namespace
+
+extern "C" {
+
+int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *stream) {
+    if (plan == nullptr || z == nullptr || subs_packed == nullptr) return LP_ERR_INVALID_ARG;
+    if (!aligned_to(z, 4) || !aligned_to(subs_packed, 4)) return LP_ERR_INVALID_ARG;
+    if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (pick_vec(plan, z, subs_packed)) {
+        case 4: return launch_partition<4>(plan, z, subs_packed, st);
+        case 2: return launch_partition<2>(plan, z, subs_packed, st);
+        default: return launch_partition<1>(plan, z, subs_packed, st);
+    }
+}
+
+int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, void *stream) {
+    if (plan == nullptr || preds_packed == nullptr || out == nullptr) return LP_ERR_INVALID_ARG;
+    if (!aligned_to(preds_packed, 4) || !aligned_to(out, 4)) return LP_ERR_INVALID_ARG;
+    if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (pick_vec(plan, preds_packed, out)) {
+        case 4: return launch_reconstruct<4>(plan, preds_packed, out, st);
+        case 2: return launch_reconstruct<2>(plan, preds_packed, out, st);
+        default: return launch_reconstruct<1>(plan, preds_packed, out, st);
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C-ABI binding.
+
+torch is used for device memory and the stream only.
+"""
+import numpy as np
+import torch
+
+from paper_2512_07350_amd import binding as lp
+from paper_2512_07350_amd import synth
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_plan(latent, patch, K, dim, overlap_patches=-1, overlap_ratio=0.0):
+    return lp.lp_plan_create(latent, patch, K, dim, overlap_patches=overlap_patches, overlap_ratio=overlap_ratio)
+
+
+def hip_partition(plan, z: np.ndarray) -> np.ndarray:
+    zd = torch.from_numpy(np.ascontiguousarray(z, dtype=np.float32)).cuda()
+    subs = torch.full((max(plan.total_elems, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    lp.lp_partition(plan, zd, subs, stream())
+    torch.cuda.synchronize()
+    return subs.cpu().numpy()[:plan.total_elems]
+
+
+def hip_reconstruct(plan, preds: np.ndarray, latent) -> np.ndarray:
+    pd = torch.from_numpy(np.ascontiguousarray(preds, dtype=np.float32)).cuda()
+    out = torch.full(tuple(latent), float("nan"), dtype=torch.float32, device="cuda")
+    lp.lp_reconstruct(plan, pd, out, stream())
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def to_dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> device tensor of dtype bfloat16 with the same bits."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def from_dev_bf16(t: torch.Tensor) -> np.ndarray:
+    """device bfloat16 tensor -> float32 numpy (exact widening)."""
+    bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return synth.bf16_bits_to_f32(bits)
+
+
+def hip_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float = 0.0) -> np.ndarray:
+    """q, k, v: uint16 [n, heads, d] token-major.  Returns float32 [n, heads, d]."""
+    n, heads, d = q.shape
+    qd, kd, vd = to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(v)
+    od = torch.full((n, heads, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lp.lp_attention(qd, kd, vd, od, n, heads, d, heads * d, d, scale, stream())
+    torch.cuda.synchronize()
+    return from_dev_bf16(od)
+
+
+# tolerance of the attention path against the fp32/fp64 oracle on N(0,1) inputs
+ATT_MAX_ABS = 2e-2
+ATT_MEAN_ABS = 2e-3
+
+
+def assert_attention_close(got: np.ndarray, want: np.ndarray, what=""):
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got)), what
+    err = np.abs(got.astype(np.float64) - want.astype(np.float64))
+    assert err.max() <= ATT_MAX_ABS, (what, float(err.max()))
+    assert err.mean() <= ATT_MEAN_ABS, (what, float(err.mean()))

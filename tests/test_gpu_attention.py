@@ -1,0 +1,145 @@
+"""lp_attention on the GPU against the CPU oracle.
+
+Tolerance (stated by the task for N(0,1) inputs, bf16 products, fp32 softmax):
+max-abs <= 2e-2 and mean-abs <= 2e-3 against the oracle's fp32 output.
+"""
+import numpy as np
+import pytest
+
+from oracle import lp_oracle as orc
+from paper_2512_07350_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("hd", [64, 128])
+@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 63, 64, 65, 200, 255, 256, 257, 320, 513, 1000])
+def test_small_full_oracle(n, hd):
+    from tests import gpu_util as g
+    heads = 3
+    q, k, v = synth.qkv_bf16(4000 + 2 * n + hd, n, heads, hd)
+    got = g.hip_attention(q, k, v)
+    want = orc.attention(q, k, v)
+    g.assert_attention_close(got, want, "n=%d hd=%d" % (n, hd))
+
+
+def test_tiny_config_partitions_full_oracle():
+    # tiny config: 2 partitions of 200 tokens, 4 heads x 64
+    from tests import gpu_util as g
+    for k_part in range(2):
+        q, k, v = synth.qkv_bf16(synth.seed_for(0, 2, k_part), 200, 4, 64)
+        g.assert_attention_close(g.hip_attention(q, k, v), orc.attention(q, k, v), "tiny k=%d" % k_part)
+
+
+def test_medium_full_oracle_spans_many_tiles():
+    # 3276 tokens (the smallest 33-frame partition along H), all rows, 2 heads
+    from tests import gpu_util as g
+    q, k, v = synth.qkv_bf16(77, 3276, 2, 128)
+    g.assert_attention_close(g.hip_attention(q, k, v), orc.attention(q, k, v), "n=3276")
+
+
+def test_explicit_scale_and_default_scale():
+    from tests import gpu_util as g
+    q, k, v = synth.qkv_bf16(78, 300, 2, 128)
+    g.assert_attention_close(g.hip_attention(q, k, v, scale=0.05), orc.attention(q, k, v, scale=0.05), "scale=.05")
+    a = g.hip_attention(q, k, v, scale=0.0)
+    b = g.hip_attention(q, k, v, scale=float(1.0 / np.sqrt(128.0)))
+    assert np.array_equal(a, b)
+
+
+def test_special_cases():
+    from tests import gpu_util as g
+    n, hd = 300, 64
+    q, k, v = synth.qkv_bf16(79, n, 2, hd)
+    vf = synth.bf16_bits_to_f32(v)
+    # zero queries -> uniform softmax -> column mean of V
+    q0 = np.zeros_like(q)
+    got = g.hip_attention(q0, k, v)
+    assert np.max(np.abs(got - vf.mean(axis=0)[None])) < 1e-2
+    # identical value rows -> that row exactly (softmax weights sum to one; bf16 of a bf16 value)
+    v1 = np.broadcast_to(v[7:8], v.shape).copy()
+    got = g.hip_attention(q, k, v1)
+    assert np.max(np.abs(got - synth.bf16_bits_to_f32(v1))) <= 2 ** -7 * np.max(np.abs(vf))
+    # one dominant key -> its value row
+    big = synth.f32_to_bf16_bits(np.full((hd,), 8.0, dtype=np.float32))
+    q2, k2 = q.copy(), k.copy()
+    q2[:] = big
+    k2[5, :] = big
+    got = g.hip_attention(q2, k2, v)
+    assert np.max(np.abs(got - vf[5][None])) < 1e-6
+    # large logits must not overflow: scores of magnitude ~ 4096
+    k3 = np.broadcast_to(big, k.shape).copy()
+    got = g.hip_attention(q2, k3, v)
+    assert np.all(np.isfinite(got))
+    assert np.max(np.abs(got - vf.mean(axis=0)[None])) < 1e-2
+
+
+def test_head_major_strides_and_in_place_views():
+    # same data laid out [heads, n, d]: stride_tok = d, stride_head = n*d
+    from tests import gpu_util as g
+    import torch
+    from paper_2512_07350_amd import binding as lp
+    n, heads, hd = 333, 3, 128
+    q, k, v = synth.qkv_bf16(80, n, heads, hd)
+    want = g.hip_attention(q, k, v)
+    qd, kd, vd = (g.to_dev_bf16(np.ascontiguousarray(a.transpose(1, 0, 2))) for a in (q, k, v))
+    od = torch.zeros((heads, n, hd), dtype=torch.bfloat16, device="cuda")
+    lp.lp_attention(qd, kd, vd, od, n, heads, hd, hd, n * hd, 0.0, g.stream())
+    torch.cuda.synchronize()
+    got = g.from_dev_bf16(od).transpose(1, 0, 2)
+    assert np.array_equal(got, want)
+
+
+def test_zero_tokens_is_a_noop():
+    from paper_2512_07350_amd import binding as lp
+    lp.lp_attention(0, 0, 0, 0, 0, 4, 64, 256, 64)
+
+
+# (workload index, partition dim): every partition of these is checked on sampled rows
+FULL_SIZE = [(1, 0), (1, 1), (1, 2), (2, 1)]
+
+
+@pytest.mark.parametrize("cfg,dim", FULL_SIZE)
+def test_full_size_partitions_sampled_rows(cfg, dim):
+    """Benchmark shapes, in the launch configuration the benchmark times; the oracle
+    evaluates sampled query rows (each over all keys)."""
+    from tests import gpu_util as g
+    w = synth.WORKLOADS[cfg]
+    pl = orc.plan(w.latent, w.patch, w.K, dim, overlap_patches=w.overlap_patches)
+    for kp, part in enumerate(pl.parts):
+        n = part.n_tokens
+        if n == 0:
+            continue
+        q, k, v = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
+        got = g.hip_attention(q, k, v)
+        rows = synth.sample_rows(n, 96, seed=kp + 10 * dim, tile=256)
+        want = orc.attention(q, k, v, rows=rows)
+        g.assert_attention_close(got[rows], want, "cfg%d %s k=%d n=%d" % (cfg, synth.DIM_NAMES[dim], kp, n))
+        assert np.all(np.isfinite(got))
+
+
+def test_full_sequence_K1_sampled_rows():
+    # the non-LP comparison of the 81-frame config: all 32760 tokens in one sequence
+    from tests import gpu_util as g
+    w = synth.WORKLOADS[2]
+    n = orc.plan(w.latent, w.patch, 1, 1, overlap_patches=0).parts[0].n_tokens
+    assert n == 32760
+    q, k, v = synth.qkv_bf16(synth.seed_for(2, 1, 15), n, w.heads, w.head_dim)
+    got = g.hip_attention(q, k, v)
+    rows = synth.sample_rows(n, 64, seed=5, tile=256)
+    g.assert_attention_close(got[rows], orc.attention(q, k, v, rows=rows), "K=1 n=32760")
+    assert np.all(np.isfinite(got))
+
+
+def test_14b_shape_sampled_rows():
+    # 720p, 40 heads: one interior partition (13230 tokens) and the first one (11340)
+    from tests import gpu_util as g
+    w = synth.WORKLOADS[3]
+    pl = orc.plan(w.latent, w.patch, w.K, 2, overlap_patches=w.overlap_patches)
+    for kp in (0, 3):
+        n = pl.parts[kp].n_tokens
+        q, k, v = synth.qkv_bf16(synth.seed_for(3, 2, kp), n, w.heads, w.head_dim)
+        got = g.hip_attention(q, k, v)
+        rows = synth.sample_rows(n, 48, seed=kp, tile=256)
+        g.assert_attention_close(got[rows], orc.attention(q, k, v, rows=rows), "14b k=%d n=%d" % (kp, n))
+        assert np.all(np.isfinite(got))

@@ -1,0 +1,112 @@
+"""lp_partition / lp_reconstruct on the GPU against the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import lp_oracle as orc
+from paper_2512_07350_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+P122 = (1, 2, 2)
+
+# (latent, patch, K, overlap patches, dims)
+CASES = [
+    ((16, 5, 16, 16), P122, 2, 1, (0, 1, 2)),            # tiny config (+ the two other dims)
+    ((16, 9, 60, 104), P122, 4, 1, (0, 1, 2)),           # 33-frame 480p, rotating
+    ((16, 21, 60, 104), P122, 4, 2, (0, 1, 2)),          # 81-frame 480p
+    ((16, 21, 90, 160), P122, 8, 2, (2,)),               # 81-frame 720p, K = 8
+    ((3, 4, 6, 10), (1, 1, 1), 3, 1, (0, 1, 2)),         # patch 1: slices only 4-byte aligned along W
+    ((2, 6, 9, 15), (2, 3, 5), 2, 1, (0, 1, 2)),         # odd extents, scalar path
+    ((5, 8, 12, 36), P122, 5, 3, (0, 1, 2)),             # overlap wider than the core: 3 partitions meet
+    ((1, 2, 2, 2), P122, 1, 0, (0, 1, 2)),               # smallest latent, K = 1
+    ((2, 3, 4, 6), P122, 7, 0, (0, 1, 2)),               # K > N: empty partitions
+]
+
+
+def _flat(cases):
+    out = []
+    for latent, patch, K, O, dims in cases:
+        for d in dims:
+            out.append(pytest.param(latent, patch, K, O, d, id="%s-K%d-O%d-%s" % ("x".join(map(str, latent)), K, O, synth.DIM_NAMES[d])))
+    return out
+
+
+@pytest.mark.parametrize("latent,patch,K,O,dim", _flat(CASES))
+def test_partition_bit_exact(latent, patch, K, O, dim):
+    from tests import gpu_util as g
+    z = synth.latent(synth.seed_for(9, dim, K), latent)
+    ref_plan = orc.plan(latent, patch, K, dim, overlap_patches=O)
+    want = orc.partition(ref_plan, z)
+    plan = g.make_plan(latent, patch, K, dim, overlap_patches=O)
+    got = g.hip_partition(plan, z)
+    assert got.shape == want.shape
+    assert got.tobytes() == want.tobytes()
+    # and on an index-coded latent, where any wrong source index shows up as a wrong value
+    zi = synth.index_coded(latent)
+    assert g.hip_partition(plan, zi).tobytes() == orc.partition(ref_plan, zi).tobytes()
+
+
+@pytest.mark.parametrize("latent,patch,K,O,dim", _flat(CASES))
+def test_reconstruct_bit_exact(latent, patch, K, O, dim):
+    from tests import gpu_util as g
+    ref_plan = orc.plan(latent, patch, K, dim, overlap_patches=O)
+    preds = synth.normal_f32(synth.seed_for(9, dim, K, tensor=5), (ref_plan.total_elems,))
+    want = orc.reconstruct(ref_plan, preds)
+    plan = g.make_plan(latent, patch, K, dim, overlap_patches=O)
+    got = g.hip_reconstruct(plan, preds, latent)
+    assert got.tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("r", [0.5, 1.0, 1.5])
+def test_reconstruct_bit_exact_with_ratio_overlap(r):
+    # r = 1.0 and 1.5 give non-dyadic ramps (Delta = 16, 26 ...) and three-way overlaps
+    from tests import gpu_util as g
+    latent = (16, 13, 60, 104)
+    for dim in range(3):
+        ref_plan = orc.plan(latent, P122, 4, dim, r=r)
+        preds = synth.normal_f32(1234 + dim, (ref_plan.total_elems,))
+        plan = g.make_plan(latent, P122, 4, dim, overlap_ratio=r)
+        assert g.hip_reconstruct(plan, preds, latent).tobytes() == orc.reconstruct(ref_plan, preds).tobytes()
+
+
+def test_roundtrip_on_device():
+    # partition then reconstruct of the same field returns it (index-coded: exactly)
+    from tests import gpu_util as g
+    import torch
+    from paper_2512_07350_amd import binding as lp
+    latent = (16, 21, 60, 104)
+    z = synth.index_coded(latent)
+    for dim in range(3):
+        plan = g.make_plan(latent, P122, 4, dim, overlap_patches=2)
+        zd = torch.from_numpy(z).cuda()
+        subs = torch.empty(plan.total_elems, dtype=torch.float32, device="cuda")
+        out = torch.empty_like(zd)
+        lp.lp_partition(plan, zd, subs, g.stream())
+        lp.lp_reconstruct(plan, subs, out, g.stream())
+        torch.cuda.synchronize()
+        assert torch.equal(out, zd)
+
+
+def test_misaligned_buffers_fall_back_to_narrower_vectors():
+    from tests import gpu_util as g
+    import torch
+    from paper_2512_07350_amd import binding as lp
+    latent = (4, 6, 12, 16)
+    z = synth.latent(77, latent)
+    for dim in range(3):
+        ref_plan = orc.plan(latent, P122, 3, dim, overlap_patches=1)
+        plan = g.make_plan(latent, P122, 3, dim, overlap_patches=1)
+        n_lat = z.size
+        for shift in (1, 2):       # buffers only 4- or 8-byte aligned
+            zbuf = torch.zeros(n_lat + 4, dtype=torch.float32, device="cuda")
+            sbuf = torch.zeros(plan.total_elems + 4, dtype=torch.float32, device="cuda")
+            obuf = torch.zeros(n_lat + 4, dtype=torch.float32, device="cuda")
+            zbuf[shift:shift + n_lat] = torch.from_numpy(z.ravel()).cuda()
+            lp.lp_partition(plan, zbuf.data_ptr() + 4 * shift, sbuf.data_ptr() + 4 * shift, g.stream())
+            lp.lp_reconstruct(plan, sbuf.data_ptr() + 4 * shift, obuf.data_ptr() + 4 * shift, g.stream())
+            torch.cuda.synchronize()
+            subs = sbuf[shift:shift + plan.total_elems].cpu().numpy()
+            assert subs.tobytes() == orc.partition(ref_plan, z).tobytes()
+            out = obuf[shift:shift + n_lat].cpu().numpy().reshape(latent)
+            assert out.tobytes() == orc.reconstruct(ref_plan, subs).tobytes()
+            assert float(sbuf[:shift].abs().sum()) == 0.0 and float(obuf[shift + n_lat:].abs().sum()) == 0.0
