@@ -66,6 +66,11 @@ def _lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("%s is missing: build it with `python -m paper_2512_07350_amd.build` "
                                "(there is no fallback path)" % LIB_PATH)
+        # One HIP runtime per process: the PyTorch wheel bundles its own libamdhip64, and
+        # device memory and streams come from PyTorch, so it has to be the runtime this
+        # library binds to.  Importing torch first makes the loader resolve the library's
+        # libamdhip64 dependency to the copy that is already mapped.
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         lib.lp_rotation_dim.argtypes = [i64]

@@ -309,16 +309,10 @@ int launch(const void *q, const void *k, const void *v, void *o, int n, int head
     const int n_qtiles = (n + kBM - 1) / kBM;
     const dim3 grid(uint32_t(n_qtiles) * uint32_t(heads));
     const float scale_log2e = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), Smem<D>::kBytes, stream,
-                       static_cast<const __bf16 *>(q), static_cast<const __bf16 *>(k),
-                       static_cast<const __bf16 *>(v), static_cast<__bf16 *>(o), n, heads, stride_tok,
-                       stride_head, scale_log2e, n_qtiles);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
-        lp::set_last_hip_error(int(e));
-        return LP_ERR_HIP;
-    }
-    return LP_OK;
+    return lp::launch_kernel(reinterpret_cast<const void *>(kern), grid, dim3(kThreads), Smem<D>::kBytes, stream,
+                             static_cast<const __bf16 *>(q), static_cast<const __bf16 *>(k),
+                             static_cast<const __bf16 *>(v), static_cast<__bf16 *>(o), n, heads, stride_tok,
+                             stride_head, scale_log2e, n_qtiles);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }

@@ -24,3 +24,21 @@ struct lp_plan {
 namespace lp {
 void set_last_hip_error(int err);
 }
+
+#ifdef __HIPCC__
+#include <hip/hip_runtime.h>
+namespace lp {
+// Launch through hipLaunchKernel so that the status is this launch's own return
+// value (hipGetLastError would also report errors other code left behind).
+template <typename... Args>
+inline int launch_kernel(const void *fn, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, Args... args) {
+    void *argv[] = {static_cast<void *>(&args)...};
+    const hipError_t e = hipLaunchKernel(fn, grid, block, argv, lds_bytes, stream);
+    if (e != hipSuccess) {
+        set_last_hip_error(int(e));
+        return LP_ERR_HIP;
+    }
+    return LP_OK;
+}
+}  // namespace lp
+#endif

@@ -187,14 +187,6 @@ int pick_vec(const lp_plan *pl, const void *a, const void *b) {
     return 1;
 }
 
-int check_launch(hipError_t err) {
-    if (err != hipSuccess) {
-        lp::set_last_hip_error(int(err));
-        return LP_ERR_HIP;
-    }
-    return LP_OK;
-}
-
 template <int VEC>
 int launch_partition(const lp_plan *pl, const float *z, float *subs, hipStream_t stream) {
     constexpr int UNROLL = 4;
@@ -213,8 +205,8 @@ int launch_partition(const lp_plan *pl, const float *z, float *subs, hipStream_t
     if (max_vec == 0) return LP_OK;
     const uint32_t per_block = kThreads * UNROLL;
     dim3 grid((max_vec + per_block - 1) / per_block, pl->K);
-    hipLaunchKernelGGL((partition_kernel<VEC, UNROLL>), grid, dim3(kThreads), 0, stream, z, subs, a);
-    return check_launch(hipGetLastError());
+    return lp::launch_kernel(reinterpret_cast<const void *>(&partition_kernel<VEC, UNROLL>), grid, dim3(kThreads), 0,
+                             stream, z, subs, a);
 }
 
 template <int VEC>
@@ -236,11 +228,9 @@ int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, hipStr
     a.inner_vec = x_per_elem ? 1 : uint32_t(pl->inner / VEC);
     a.inner_div = make_fastdiv(a.inner_vec);
     dim3 grid((a.n_vec + kThreads - 1) / kThreads);
-    if (x_per_elem)
-        hipLaunchKernelGGL((reconstruct_kernel<VEC, true>), grid, dim3(kThreads), 0, stream, preds, out, a);
-    else
-        hipLaunchKernelGGL((reconstruct_kernel<VEC, false>), grid, dim3(kThreads), 0, stream, preds, out, a);
-    return check_launch(hipGetLastError());
+    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true>)
+                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false>);
+    return lp::launch_kernel(fn, grid, dim3(kThreads), 0, stream, preds, out, a);
 }
 
 // The kernels index with 32-bit vector counts; 2^31 vectors is far beyond any latent.
