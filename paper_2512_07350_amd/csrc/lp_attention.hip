@@ -1,22 +1,35 @@
 // lp_attention: non-causal multi-head self-attention over the patch tokens of one
 // sub-latent (supplement, proof of Theorem 1, step 3: inside a sub-latent the DiT
 // blocks attend globally over all of its positions), as a flash-style kernel for
-// gfx950: bf16 MFMA 32x32x16 for both products, binary32 online softmax, K and
-// V^T tiles staged through LDS.
+// gfx950: bf16 MFMA 32x32x16 for both products, binary32 online softmax, K and V
+// tiles streamed global -> LDS without passing through registers.
 //
-// Work decomposition.  One workgroup = 4 wavefronts = 256 query rows of one
-// head; each wavefront owns 64 query rows (two 32-column MFMA blocks) and walks
-// all keys in tiles of 64.  Per tile it forms the TRANSPOSED scores
-//     S^T[key, query] = K_tile . Q^T        (A = K rows from LDS, B = Q in registers)
-// so that in the MFMA accumulator layout a lane holds 16 scores of ONE query:
-// row maxima and row sums are in-lane reductions plus one exchange between the
-// two half-waves, the rescale factor of the running output is a per-lane scalar,
-// and the bf16 probabilities are already laid out as the B operand of
-//     O^T[d, query] += V^T_tile . P^T       (A = V^T rows from LDS).
-// The key order inside a 32-key block is permuted (bits 2 and 3 of the MFMA row
-// index swapped when K rows are read) so that the 8 probabilities a lane feeds
-// to one MFMA belong to 8 consecutive keys, which makes the V^T operand a single
-// 16-byte LDS read.  V is transposed on its way from global memory into LDS.
+// Work decomposition.  One workgroup = 4 wavefronts = 256 query rows of one head;
+// each wavefront owns 64 query rows (two 32-column MFMA blocks) and walks all keys
+// in rounds of 32.  Per round it forms the TRANSPOSED scores
+//     S^T[key, query] = K . Q^T            (A = K rows from LDS, B = Q in registers)
+// so that in the MFMA accumulator layout a lane holds 16 scores of ONE query: the
+// row maximum and row sum are in-lane reductions, the rescale factor of the running
+// output is a per-lane scalar, and the bf16 probabilities are already laid out as
+// the B operand of
+//     O^T[d, query] += V^T . P^T           (A = V^T, read transposed from LDS).
+//
+// Details that matter for speed:
+//  * Q is multiplied by scale*log2(e) once and re-rounded to bf16, and the score
+//    accumulators start at -m (m = running maximum, log2 units), so a probability
+//    is a bare exp2 of the accumulator.
+//  * The running maximum is only raised when some score exceeds it by more than
+//    kRescaleThreshold; probabilities then stay below 2^kRescaleThreshold and the
+//    output accumulators are rescaled in a rarely taken, wave-uniform branch.
+//  * The score product of round r+1 is issued before the softmax of round r, so
+//    MFMA and VALU work of one wavefront overlap.
+//  * The key order inside a 32-key round is permuted (bits 2 and 3 of the MFMA row
+//    index swapped when K rows are read) so that the 8 probabilities a lane feeds
+//    to one MFMA belong to 8 consecutive keys; V^T operands then come from two
+//    ds_read_b64_tr_b16 (transposing LDS reads) of the row-major V tile.
+//  * K/V tiles go global -> LDS with global_load_lds_dwordx4 (kStages tiles
+//    resident), with XOR swizzles of the 16-byte granules chosen so that the K
+//    reads (ds_read_b128) and the V reads are free of bank conflicts.
 #include <hip/hip_runtime.h>
 
 #include "lp_internal.h"
@@ -24,54 +37,244 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
-constexpr int kQPerWave = 64;                 // two MFMA column blocks of 32 queries
-constexpr int kBM = kWaves * kQPerWave;       // query rows per workgroup
-constexpr int kBN = 64;                       // keys per tile
-constexpr int kPad = 8;                       // bf16 elements of row padding in LDS (16 bytes)
+#define LP_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+
+constexpr int kBM = 256;                      // query rows per workgroup
+// A wavefront owns NB blocks of 32 query rows; the workgroup has kBM / (32 NB) wavefronts.
+constexpr int waves_of(int nb) { return kBM / (32 * nb); }
+constexpr int kBlocksPerWave = 1;             // NB used by lp_attention
+constexpr int kBN = 64;                       // keys per LDS tile (two rounds of 32)
+constexpr int kStages = 3;                    // LDS tiles resident (>= 3)
 constexpr float kRescaleThreshold = 8.0f;     // log2 units the running max may lag behind
 
-template <int D>
-struct Smem {
-    static constexpr int kRowK = D + kPad;            // K tile row (one key), in bf16
-    static constexpr int kRowV = kBN + kPad;          // V^T tile row (one d), in bf16
-    static constexpr int kTileK = kBN * kRowK;
-    static constexpr int kTileV = D * kRowV;
-    static constexpr int kBytes = 2 * (kTileK + kTileV) * 2;   // double buffered
+template <int D, int NB>
+struct Tile {
+    static constexpr int kWaves = waves_of(NB);
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kGran = kRowBytes / 16;            // 16-byte granules per row
+    static constexpr int kTileBytes = kBN * kRowBytes;      // one K or one V tile
+    static constexpr int kStageBytes = 2 * kTileBytes;      // K tile then V tile
+    static constexpr int kBytes = kStages * kStageBytes;
+    static constexpr int kRowsPerInstr = 1024 / kRowBytes;  // rows one wave-wide 16-byte load covers
+    static constexpr int kInstrPerTile = kBN / kRowsPerInstr;
+    static constexpr int kLoadsPerWave = 2 * kInstrPerTile / kWaves;   // K and V, per tile
+    // granule XOR masks; reader and writer use the same functions
+    __device__ static int swz_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+    __device__ static int swz_v(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row & 3) >> 1); }
 };
 
 union Pack16 {
     uint4 u;
     bf16x8 v;
+    bf16x4 h[2];
+    bf16x2 p[4];
 };
 
-__device__ __forceinline__ float half_swap(float x) {
-    // value held by the lane 32 away (the other half-wave)
-    return __shfl_xor(x, 32, 64);
+__device__ __forceinline__ float other_half(float x) {
+    return __shfl_xor(x, 32, 64);   // value held by the lane 32 away
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+__device__ __forceinline__ bf16x2 to_bf16x2(float lo, float hi) {
     f32x2 f = {lo, hi};
-    bf16x2 b = __builtin_convertvector(f, bf16x2);
-    return __builtin_bit_cast(uint32_t, b);
+    return __builtin_convertvector(f, bf16x2);
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 1) void attention_kernel(
+// Wait until at most `pending` of this wave's global->LDS loads are still in flight.
+template <int PENDING>
+__device__ __forceinline__ void wait_tile_loads() {
+    static_assert(PENDING >= 0 && PENDING < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
+}
+
+// Per-lane constants of the tile traffic.
+struct LaneCtx {
+    const __bf16 *kh, *vh;   // K and V of this head
+    int64_t stride_tok;
+    int n, n_tiles, n_rounds;
+    int wave;                // wave index inside the workgroup (wave-uniform)
+    int half;                // lane / 32
+    int krow;                // K row this lane feeds to the MFMA: lane%32 with bits 2 and 3 swapped
+    int vj, vg;              // lane%16 and (lane/16)%2 for the transposing V reads
+    int ld_row, ld_gran;     // row and physical granule this lane fills in a 1024-byte load block
+};
+
+// global -> LDS loads of one K/V tile.  One wave-wide instruction moves 1024 bytes
+// (lane L fills bytes 16L..16L+15 of the block); waves take blocks round robin.
+template <int D, int NB>
+__device__ __forceinline__ void issue_tile(unsigned char *smem, const LaneCtx &c, int tile) {
+    using T = Tile<D, NB>;
+    unsigned char *stage = smem + (tile % kStages) * T::kStageBytes;
+    const int key0 = tile * kBN;
+#pragma unroll
+    for (int i = 0; i < T::kInstrPerTile / T::kWaves; ++i) {
+        const int instr = c.wave + i * T::kWaves;
+        const int row = instr * T::kRowsPerInstr + c.ld_row;       // row inside the tile
+        int key = key0 + row;
+        key = key < c.n ? key : c.n - 1;                            // rows past the end repeat the last key
+        const int64_t goff = int64_t(key) * c.stride_tok;
+        // (operands go through plainly typed locals: the builtin is checked where it is written)
+        const int gk = c.ld_gran ^ T::swz_k(row), gv = c.ld_gran ^ T::swz_v(row);
+        const __bf16 *src_k = c.kh + goff + 8 * gk;
+        const __bf16 *src_v = c.vh + goff + 8 * gv;
+        unsigned char *dst_k = stage + instr * 1024;
+        unsigned char *dst_v = dst_k + T::kTileBytes;
+        __builtin_amdgcn_global_load_lds(src_k, LP_LDS_PTR(void, dst_k), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(src_v, LP_LDS_PTR(void, dst_v), 16, 0, 0);
+    }
+}
+
+// S^T of round r (32 keys) for both query blocks.
+template <int D, int NB>
+__device__ __forceinline__ void score_round(const unsigned char *smem, const LaneCtx &c, int r,
+                                            const bf16x8 (&qreg)[NB][D / 16], f32x16 (&s)[NB]) {
+    using T = Tile<D, NB>;
+    const int tile = r / 2, sub = r % 2;
+    const unsigned char *kt = smem + (tile % kStages) * T::kStageBytes;
+    const int row = sub * 32 + c.krow;
+    const unsigned char *rp = kt + row * T::kRowBytes;
+    const int sw = T::swz_k(row);
+    f32x16 zero16;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+        const bf16x8 a = *LP_LDS_PTR(const bf16x8, rp + 16 * ((2 * kk + c.half) ^ sw));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[nb][kk], kk == 0 ? zero16 : s[nb], 0, 0, 0);
+    }
+}
+
+// Keys past the end get score -inf.  Accumulator register i of a lane is key
+// 32*r + 16*(i/8) + 8*half + i%8.
+template <int NB>
+__device__ __forceinline__ void mask_round(const LaneCtx &c, int r, f32x16 (&s)[NB]) {
+    const int kbase = r * 32 + c.half * 8;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (kbase + 16 * (i / 8) + (i % 8) >= c.n) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) s[nb][i] = -INFINITY;
+        }
+    }
+}
+
+// O^T += V^T . P^T for round r.  Inside a group of 16 lanes, lane j supplies the 8-byte
+// chunk (row j/4, columns 4*(j%4)..+3) to the transposing read and receives column j of
+// that 4x16 block, i.e. 4 consecutive keys of one d.
+template <int D, int NB>
+__device__ __forceinline__ void pv_round(const unsigned char *smem, const LaneCtx &c, int r,
+                                         const bf16x8 (&p)[NB][2], f32x16 (&acc)[D / 32][NB]) {
+    using T = Tile<D, NB>;
+    const int tile = r / 2, sub = r % 2;
+    const unsigned char *vt = smem + (tile % kStages) * T::kStageBytes + T::kTileBytes;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int row0 = sub * 32 + ks * 16 + c.half * 8 + c.vj / 4;      // + 4 for the second read
+        const unsigned char *r0 = vt + row0 * T::kRowBytes + 8 * ((c.vj % 4) % 2);
+        const unsigned char *r1 = r0 + 4 * T::kRowBytes;
+        const int sw0 = T::swz_v(row0), sw1 = T::swz_v(row0 + 4);
+#pragma unroll
+        for (int mb = 0; mb < D / 32; ++mb) {
+            const int gran = 4 * mb + 2 * c.vg + (c.vj % 4) / 2;
+            Pack16 a;
+            a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, r0 + 16 * (gran ^ sw0)));
+            a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, r1 + 16 * (gran ^ sw1)));
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, p[nb][ks], acc[mb][nb], 0, 0, 0);
+        }
+    }
+}
+
+__device__ __forceinline__ float max16(const f32x16 &s) {
+    float t = s[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) t = fmaxf(t, s[i]);
+    return t;
+}
+
+// One round: issue S^T of round r+1 (MFMA), then softmax of round r (VALU), then PV of
+// round r (MFMA).  s_cur / s_nxt swap roles from round to round.
+template <int D, int NB>
+__device__ __forceinline__ void round_body(unsigned char *smem, const LaneCtx &c, int r,
+                                           const bf16x8 (&qreg)[NB][D / 16], f32x16 (&s_cur)[NB],
+                                           f32x16 (&s_nxt)[NB], f32x16 (&acc)[D / 32][NB],
+                                           float (&m_run)[NB], float (&l_run)[NB]) {
+    using T = Tile<D, NB>;
+    if (r + 1 < c.n_rounds) {
+        if ((r & 1) == 1) {
+            // The next round opens tile t.  Tiles t .. t+kStages-3 are in flight; t must
+            // have landed.  After the barrier every wave has left tile t-2, whose stage
+            // then takes tile t+kStages-2.  (Tile t-1 still feeds this round's V reads.)
+            const int t = (r + 1) / 2;
+            if (t + kStages - 3 < c.n_tiles)
+                wait_tile_loads<(kStages - 3) * T::kLoadsPerWave>();
+            else
+                wait_tile_loads<0>();          // near the end fewer tiles are in flight
+            __syncthreads();
+            if (t + kStages - 2 < c.n_tiles) issue_tile<D, NB>(smem, c, t + kStages - 2);
+        }
+        score_round<D, NB>(smem, c, r + 1, qreg, s_nxt);
+    }
+    if ((r + 1) * 32 > c.n) mask_round<NB>(c, r, s_cur);
+
+    // ---- lazy running maximum: only act when some score is far above it
+    bool raise = false;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) raise = raise || (max16(s_cur[nb]) - m_run[nb] > kRescaleThreshold);
+    if (__any(raise)) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float tmax = max16(s_cur[nb]);
+            tmax = fmaxf(tmax, other_half(tmax));
+            const float m_new = fmaxf(m_run[nb], tmax);      // the maximum never goes down
+            const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+            m_run[nb] = m_new;
+            l_run[nb] *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[mb][nb][i] *= alpha;
+        }
+    }
+
+    // ---- probabilities, rounded to bf16; the row sum adds the rounded values
+    bf16x8 p[NB][2];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        Pack16 lo, hi;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        const float m = m_run[nb];
+        float l = l_run[nb];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s_cur[nb][2 * e] - m), __builtin_amdgcn_exp2f(s_cur[nb][2 * e + 1] - m));
+            hi.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s_cur[nb][8 + 2 * e] - m), __builtin_amdgcn_exp2f(s_cur[nb][8 + 2 * e + 1] - m));
+            l = __builtin_amdgcn_fdot2_f32_bf16(lo.p[e], ones, l, false);
+            l = __builtin_amdgcn_fdot2_f32_bf16(hi.p[e], ones, l, false);
+        }
+        l_run[nb] = l;
+        p[nb][0] = lo.v;
+        p[nb][1] = hi.v;
+    }
+    pv_round<D, NB>(smem, c, r, p, acc);
+}
+
+template <int D, int NB>
+__global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
     __bf16 *__restrict__ o, int n, int heads, int64_t stride_tok, int64_t stride_head,
     float scale_log2e, int n_qtiles) {
-    using S = Smem<D>;
+    using T = Tile<D, NB>;
     constexpr int KS = D / 16;        // MFMA steps along d for S^T
     constexpr int MB = D / 32;        // 32-row blocks of O^T
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
-    // layout: K tile 0, K tile 1, V^T tile 0, V^T tile 1
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // Workgroup -> (head, query tile).  Consecutive workgroup ids are dealt round
     // robin to the 8 XCDs; remap so each XCD works on a contiguous range of
@@ -85,196 +288,86 @@ __global__ __launch_bounds__(kThreads, 1) void attention_kernel(
     const int qtile = logical % n_qtiles;
 
     const int tid = threadIdx.x;
-    const int wave = tid / 64;
     const int lane = tid % 64;
     const int col = lane % 32;        // MFMA column (query) / A-operand row
-    const int half = lane / 32;
-
     const int64_t head_off = int64_t(head) * stride_head;
     const __bf16 *qh = q + head_off;
-    const __bf16 *kh = k + head_off;
-    const __bf16 *vh = v + head_off;
     __bf16 *oh = o + head_off;
 
-    // ---- Q^T operands: lane holds, for query `col` of block nb, d = 16*kk + 8*half .. +7
-    const int q0 = qtile * kBM + wave * kQPerWave;
-    bf16x8 qreg[2][KS];
+    LaneCtx c;
+    c.kh = k + head_off;
+    c.vh = v + head_off;
+    c.stride_tok = stride_tok;
+    c.n = n;
+    c.n_tiles = (n + kBN - 1) / kBN;
+    c.n_rounds = (n + 31) / 32;
+    c.wave = __builtin_amdgcn_readfirstlane(tid / 64);
+    c.half = lane / 32;
+    c.krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
+    c.vj = lane % 16;
+    c.vg = (lane / 16) % 2;
+    c.ld_row = lane / T::kGran;
+    c.ld_gran = lane % T::kGran;
+
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int t = 0; t < kStages - 1; ++t)
+        if (t < c.n_tiles) issue_tile<D, NB>(smem, c, t);
+
+    // ---- Q^T operands, pre-multiplied by scale*log2(e): lane holds, for query `col`
+    // of block nb, d = 16*kk + 8*half .. +7
+    const int q0 = qtile * kBM + c.wave * (32 * NB);
+    bf16x8 qreg[NB][KS];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
         const int qi = q0 + nb * 32 + col;
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
             Pack16 t;
             t.u = make_uint4(0, 0, 0, 0);
-            if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + half * 8);
+            if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + c.half * 8);
+            const uint32_t w[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)   // a bf16 is the upper half of the binary32 with the same value
+                t.p[e] = to_bf16x2(__uint_as_float(w[e] << 16) * scale_log2e, __uint_as_float(w[e] & 0xffff0000u) * scale_log2e);
             qreg[nb][kk] = t.v;
         }
     }
 
-    f32x16 acc[MB][2];
+    f32x16 acc[MB][NB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.0f;
-    float m_run[2] = {-INFINITY, -INFINITY};   // running max, raw score units
-    float l_run[2] = {0.0f, 0.0f};             // this lane's share of the running sum
+    float m_run[NB];                  // running maximum (log2 units), common to both half-waves
+    float l_run[NB];                  // this lane's share of the running sum
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) l_run[nb] = 0.0f;
 
-    // ---- tile loader: global -> registers -> LDS
-    constexpr int kKChunks = kBN * (D / 8) / kThreads;    // 16-byte chunks of K per thread
-    constexpr int kVUnits = (kBN / 4) * (D / 8);          // (4 keys x 8 d) units of V per tile
-    uint4 kst[kKChunks];
-    uint4 vst[4];
-    const int v_kg = tid % 16;        // key group (4 keys)
-    const int v_dc = tid / 16;        // d chunk (8 d)
-
-    auto load_tile = [&](int key0) {
-#pragma unroll
-        for (int c = 0; c < kKChunks; ++c) {
-            const int id = tid + c * kThreads;
-            const int row = id / (D / 8), cc = id % (D / 8);
-            const int key = key0 + row;
-            kst[c] = make_uint4(0, 0, 0, 0);
-            if (key < n) kst[c] = *reinterpret_cast<const uint4 *>(kh + int64_t(key) * stride_tok + cc * 8);
-        }
-        if (tid < kVUnits) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int key = key0 + v_kg * 4 + j;
-                vst[j] = make_uint4(0, 0, 0, 0);
-                if (key < n) vst[j] = *reinterpret_cast<const uint4 *>(vh + int64_t(key) * stride_tok + v_dc * 8);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        __bf16 *ksb = smem + buf * S::kTileK;
-#pragma unroll
-        for (int c = 0; c < kKChunks; ++c) {
-            const int id = tid + c * kThreads;
-            const int row = id / (D / 8), cc = id % (D / 8);
-            *reinterpret_cast<uint4 *>(ksb + row * S::kRowK + cc * 8) = kst[c];
-        }
-        if (tid < kVUnits) {
-            __bf16 *vtb = smem + 2 * S::kTileK + buf * S::kTileV;
-            const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&vst[0]);
-            const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&vst[1]);
-            const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&vst[2]);
-            const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&vst[3]);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                // dword w of a row holds d = 2w (low half) and 2w+1 (high half)
-                uint2 even, odd;
-                even.x = (w0[w] & 0xffffu) | (w1[w] << 16);
-                even.y = (w2[w] & 0xffffu) | (w3[w] << 16);
-                odd.x = (w0[w] >> 16) | (w1[w] & 0xffff0000u);
-                odd.y = (w2[w] >> 16) | (w3[w] & 0xffff0000u);
-                const int drow = v_dc * 8 + 2 * w;
-                *reinterpret_cast<uint2 *>(vtb + drow * S::kRowV + v_kg * 4) = even;
-                *reinterpret_cast<uint2 *>(vtb + (drow + 1) * S::kRowV + v_kg * 4) = odd;
-            }
-        }
-    };
-
-    const int n_tiles = (n + kBN - 1) / kBN;
-    load_tile(0);
-    store_tile(0);
+    // ---- round 0 fixes the initial maximum
+    wait_tile_loads<0>();
     __syncthreads();
+    f32x16 s_a[NB], s_b[NB];
+    score_round<D, NB>(smem, c, 0, qreg, s_a);
+    if (n < 32) mask_round<NB>(c, 0, s_a);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const float tmax = max16(s_a[nb]);
+        m_run[nb] = fmaxf(tmax, other_half(tmax));
+        s_b[nb] = s_a[nb];
+    }
 
-    // A-operand row of K this lane reads: bits 2 and 3 of `col` swapped
-    const int krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
-
-    for (int jt = 0; jt < n_tiles; ++jt) {
-        const int buf = jt & 1;
-        const int key0 = jt * kBN;
-        const bool has_next = jt + 1 < n_tiles;
-        if (has_next) load_tile(key0 + kBN);
-        const __bf16 *ksb = smem + buf * S::kTileK;
-        const __bf16 *vtb = smem + 2 * S::kTileK + buf * S::kTileV;
-        const bool ragged = key0 + kBN > n;
-
-#pragma unroll
-        for (int sub = 0; sub < kBN / 32; ++sub) {
-            // ---- S^T = K . Q^T for 32 keys x 64 queries
-            f32x16 s[2];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[nb][r] = 0.0f;
-            const __bf16 *krow_ptr = ksb + (sub * 32 + krow) * S::kRowK + half * 8;
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(krow_ptr + kk * 16);
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][kk], s[0], 0, 0, 0);
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][kk], s[1], 0, 0, 0);
-            }
-            // accumulator register r of this lane is key  key0 + 32*sub + 16*(r/8) + 8*half + r%8
-            if (ragged) {
-                const int kbase = key0 + sub * 32 + half * 8;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = kbase + 16 * (r / 8) + (r % 8);
-                    if (key >= n) {
-                        s[0][r] = -INFINITY;
-                        s[1][r] = -INFINITY;
-                    }
-                }
-            }
-            // ---- online softmax (base 2), lazily rescaled
-            bf16x8 p[2][2];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                float tmax = s[nb][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[nb][r]);
-                tmax = fmaxf(tmax, half_swap(tmax));
-                const bool need = (tmax - m_run[nb]) * scale_log2e > kRescaleThreshold;
-                if (__any(need)) {
-                    const float m_new = fmaxf(m_run[nb], tmax);
-                    const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_new) * scale_log2e);
-                    m_run[nb] = m_new;
-                    l_run[nb] *= alpha;
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) acc[mb][nb][r] *= alpha;
-                }
-                const float mc = m_run[nb] * scale_log2e;
-                float e[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(fmaf(s[nb][r], scale_log2e, -mc));
-                Pack16 lo, hi;
-                lo.u = make_uint4(pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]), pack_bf16(e[6], e[7]));
-                hi.u = make_uint4(pack_bf16(e[8], e[9]), pack_bf16(e[10], e[11]), pack_bf16(e[12], e[13]), pack_bf16(e[14], e[15]));
-                p[nb][0] = lo.v;
-                p[nb][1] = hi.v;
-                float psum = 0.0f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) psum += e[r];
-                l_run[nb] += psum;
-            }
-            // ---- O^T += V^T . P^T
-            const __bf16 *vrow_ptr = vtb + col * S::kRowV + sub * 32 + half * 8;
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vrow_ptr + mb * 32 * S::kRowV + ks * 16);
-                    acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[0][ks], acc[mb][0], 0, 0, 0);
-                    acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[1][ks], acc[mb][1], 0, 0, 0);
-                }
-            }
-        }
-
-        if (has_next) store_tile(buf ^ 1);
-        __syncthreads();
+    for (int r = 0; r < c.n_rounds; r += 2) {
+        round_body<D, NB>(smem, c, r, qreg, s_a, s_b, acc, m_run, l_run);
+        if (r + 1 < c.n_rounds) round_body<D, NB>(smem, c, r + 1, qreg, s_b, s_a, acc, m_run, l_run);
     }
 
     // ---- normalise and store: lane holds, for query `col` of block nb, rows
-    // d = 32*mb + 8*(r/4) + 4*half + r%4 of O^T
+    // d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const float l_tot = l_run[nb] + half_swap(l_run[nb]);
+    for (int nb = 0; nb < NB; ++nb) {
+        const float l_tot = l_run[nb] + other_half(l_run[nb]);
         const float inv = 1.0f / l_tot;
         const int qi = q0 + nb * 32 + col;
         if (qi < n) {
@@ -283,23 +376,23 @@ __global__ __launch_bounds__(kThreads, 1) void attention_kernel(
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    uint2 w;
-                    w.x = pack_bf16(acc[mb][nb][4 * g + 0] * inv, acc[mb][nb][4 * g + 1] * inv);
-                    w.y = pack_bf16(acc[mb][nb][4 * g + 2] * inv, acc[mb][nb][4 * g + 3] * inv);
-                    *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + half * 4) = w;
+                    union { uint2 u; bf16x2 p[2]; } w;
+                    w.p[0] = to_bf16x2(acc[mb][nb][4 * g + 0] * inv, acc[mb][nb][4 * g + 1] * inv);
+                    w.p[1] = to_bf16x2(acc[mb][nb][4 * g + 2] * inv, acc[mb][nb][4 * g + 3] * inv);
+                    *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + c.half * 4) = w.u;
                 }
         }
     }
 }
 
-template <int D>
+template <int D, int NB>
 int launch(const void *q, const void *k, const void *v, void *o, int n, int heads, int64_t stride_tok,
            int64_t stride_head, float scale, hipStream_t stream) {
     static bool attr_set = false;   // per process; the attribute is per function
-    auto kern = attention_kernel<D>;
+    auto kern = attention_kernel<D, NB>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Smem<D>::kBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, Tile<D, NB>::kBytes);
         if (e != hipSuccess) {
             lp::set_last_hip_error(int(e));
             return LP_ERR_HIP;
@@ -309,7 +402,7 @@ int launch(const void *q, const void *k, const void *v, void *o, int n, int head
     const int n_qtiles = (n + kBM - 1) / kBM;
     const dim3 grid(uint32_t(n_qtiles) * uint32_t(heads));
     const float scale_log2e = scale * 1.4426950408889634f;
-    return lp::launch_kernel(reinterpret_cast<const void *>(kern), grid, dim3(kThreads), Smem<D>::kBytes, stream,
+    return lp::launch_kernel(reinterpret_cast<const void *>(kern), grid, dim3(waves_of(NB) * 64), Tile<D, NB>::kBytes, stream,
                              static_cast<const __bf16 *>(q), static_cast<const __bf16 *>(k),
                              static_cast<const __bf16 *>(v), static_cast<__bf16 *>(o), n, heads, stride_tok,
                              stride_head, scale_log2e, n_qtiles);
@@ -337,6 +430,6 @@ extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o
     if (!(scale > 0.0f)) scale = 1.0f / sqrtf(float(head_dim));
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (head_dim == 128)
-        return launch<128>(q, k, v, o, int(n_tokens), heads, stride_tok, stride_head, scale, st);
-    return launch<64>(q, k, v, o, int(n_tokens), heads, stride_tok, stride_head, scale, st);
+        return launch<128, kBlocksPerWave>(q, k, v, o, int(n_tokens), heads, stride_tok, stride_head, scale, st);
+    return launch<64, kBlocksPerWave>(q, k, v, o, int(n_tokens), heads, stride_tok, stride_head, scale, st);
 }
