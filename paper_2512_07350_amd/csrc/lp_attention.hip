@@ -49,7 +49,7 @@ constexpr int kBM = 256;                      // query rows per workgroup
 constexpr int waves_of(int nb) { return kBM / (32 * nb); }
 constexpr int kBlocksPerWave = 1;             // NB used by lp_attention
 constexpr int kBN = 64;                       // keys per LDS tile (two rounds of 32)
-constexpr int kStages = 3;                    // LDS tiles resident (>= 3)
+constexpr int kStages = 4;                    // LDS stages: three tiles in use plus one arriving
 constexpr float kRescaleThreshold = 8.0f;     // log2 units the running max may lag behind
 
 template <int D, int NB>
@@ -91,105 +91,10 @@ __device__ __forceinline__ void wait_tile_loads() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
 }
 
-// Per-lane constants of the tile traffic.
-struct LaneCtx {
-    const __bf16 *kh, *vh;   // K and V of this head
-    int64_t stride_tok;
-    int n, n_tiles, n_rounds;
-    int wave;                // wave index inside the workgroup (wave-uniform)
-    int half;                // lane / 32
-    int krow;                // K row this lane feeds to the MFMA: lane%32 with bits 2 and 3 swapped
-    int vj, vg;              // lane%16 and (lane/16)%2 for the transposing V reads
-    int ld_row, ld_gran;     // row and physical granule this lane fills in a 1024-byte load block
-};
-
-// global -> LDS loads of one K/V tile.  One wave-wide instruction moves 1024 bytes
-// (lane L fills bytes 16L..16L+15 of the block); waves take blocks round robin.
-template <int D, int NB>
-__device__ __forceinline__ void issue_tile(unsigned char *smem, const LaneCtx &c, int tile) {
-    using T = Tile<D, NB>;
-    unsigned char *stage = smem + (tile % kStages) * T::kStageBytes;
-    const int key0 = tile * kBN;
-#pragma unroll
-    for (int i = 0; i < T::kInstrPerTile / T::kWaves; ++i) {
-        const int instr = c.wave + i * T::kWaves;
-        const int row = instr * T::kRowsPerInstr + c.ld_row;       // row inside the tile
-        int key = key0 + row;
-        key = key < c.n ? key : c.n - 1;                            // rows past the end repeat the last key
-        const int64_t goff = int64_t(key) * c.stride_tok;
-        // (operands go through plainly typed locals: the builtin is checked where it is written)
-        const int gk = c.ld_gran ^ T::swz_k(row), gv = c.ld_gran ^ T::swz_v(row);
-        const __bf16 *src_k = c.kh + goff + 8 * gk;
-        const __bf16 *src_v = c.vh + goff + 8 * gv;
-        unsigned char *dst_k = stage + instr * 1024;
-        unsigned char *dst_v = dst_k + T::kTileBytes;
-        __builtin_amdgcn_global_load_lds(src_k, LP_LDS_PTR(void, dst_k), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(src_v, LP_LDS_PTR(void, dst_v), 16, 0, 0);
-    }
-}
-
-// S^T of round r (32 keys) for both query blocks.
-template <int D, int NB>
-__device__ __forceinline__ void score_round(const unsigned char *smem, const LaneCtx &c, int r,
-                                            const bf16x8 (&qreg)[NB][D / 16], f32x16 (&s)[NB]) {
-    using T = Tile<D, NB>;
-    const int tile = r / 2, sub = r % 2;
-    const unsigned char *kt = smem + (tile % kStages) * T::kStageBytes;
-    const int row = sub * 32 + c.krow;
-    const unsigned char *rp = kt + row * T::kRowBytes;
-    const int sw = T::swz_k(row);
-    f32x16 zero16;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 a = *LP_LDS_PTR(const bf16x8, rp + 16 * ((2 * kk + c.half) ^ sw));
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[nb][kk], kk == 0 ? zero16 : s[nb], 0, 0, 0);
-    }
-}
-
-// Keys past the end get score -inf.  Accumulator register i of a lane is key
-// 32*r + 16*(i/8) + 8*half + i%8.
-template <int NB>
-__device__ __forceinline__ void mask_round(const LaneCtx &c, int r, f32x16 (&s)[NB]) {
-    const int kbase = r * 32 + c.half * 8;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        if (kbase + 16 * (i / 8) + (i % 8) >= c.n) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) s[nb][i] = -INFINITY;
-        }
-    }
-}
-
-// O^T += V^T . P^T for round r.  Inside a group of 16 lanes, lane j supplies the 8-byte
-// chunk (row j/4, columns 4*(j%4)..+3) to the transposing read and receives column j of
-// that 4x16 block, i.e. 4 consecutive keys of one d.
-template <int D, int NB>
-__device__ __forceinline__ void pv_round(const unsigned char *smem, const LaneCtx &c, int r,
-                                         const bf16x8 (&p)[NB][2], f32x16 (&acc)[D / 32][NB]) {
-    using T = Tile<D, NB>;
-    const int tile = r / 2, sub = r % 2;
-    const unsigned char *vt = smem + (tile % kStages) * T::kStageBytes + T::kTileBytes;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int row0 = sub * 32 + ks * 16 + c.half * 8 + c.vj / 4;      // + 4 for the second read
-        const unsigned char *r0 = vt + row0 * T::kRowBytes + 8 * ((c.vj % 4) % 2);
-        const unsigned char *r1 = r0 + 4 * T::kRowBytes;
-        const int sw0 = T::swz_v(row0), sw1 = T::swz_v(row0 + 4);
-#pragma unroll
-        for (int mb = 0; mb < D / 32; ++mb) {
-            const int gran = 4 * mb + 2 * c.vg + (c.vj % 4) / 2;
-            Pack16 a;
-            a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, r0 + 16 * (gran ^ sw0)));
-            a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, r1 + 16 * (gran ^ sw1)));
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, p[nb][ks], acc[mb][nb], 0, 0, 0);
-        }
-    }
+// LDS accesses below use 32-bit LDS byte addresses held in registers.
+template <typename V>
+__device__ __forceinline__ V lds_load(uint32_t addr) {
+    return *LP_LDS_PTR(const V, uintptr_t(addr));
 }
 
 __device__ __forceinline__ float max16(const f32x16 &s) {
@@ -199,39 +104,91 @@ __device__ __forceinline__ float max16(const f32x16 &s) {
     return t;
 }
 
-// One round: issue S^T of round r+1 (MFMA), then softmax of round r (VALU), then PV of
-// round r (MFMA).  s_cur / s_nxt swap roles from round to round.
+// What a lane needs to know to move and read tiles; everything here is fixed for the
+// whole kernel.
 template <int D, int NB>
-__device__ __forceinline__ void round_body(unsigned char *smem, const LaneCtx &c, int r,
-                                           const bf16x8 (&qreg)[NB][D / 16], f32x16 (&s_cur)[NB],
-                                           f32x16 (&s_nxt)[NB], f32x16 (&acc)[D / 32][NB],
-                                           float (&m_run)[NB], float (&l_run)[NB]) {
+struct Lane {
     using T = Tile<D, NB>;
-    if (r + 1 < c.n_rounds) {
-        if ((r & 1) == 1) {
-            // The next round opens tile t.  Tiles t .. t+kStages-3 are in flight; t must
-            // have landed.  After the barrier every wave has left tile t-2, whose stage
-            // then takes tile t+kStages-2.  (Tile t-1 still feeds this round's V reads.)
-            const int t = (r + 1) / 2;
-            if (t + kStages - 3 < c.n_tiles)
-                wait_tile_loads<(kStages - 3) * T::kLoadsPerWave>();
-            else
-                wait_tile_loads<0>();          // near the end fewer tiles are in flight
-            __syncthreads();
-            if (t + kStages - 2 < c.n_tiles) issue_tile<D, NB>(smem, c, t + kStages - 2);
-        }
-        score_round<D, NB>(smem, c, r + 1, qreg, s_nxt);
-    }
-    if ((r + 1) * 32 > c.n) mask_round<NB>(c, r, s_cur);
+    static constexpr int kLd = T::kInstrPerTile / T::kWaves;   // K (and V) load instructions per wave per tile
+    __amdgpu_buffer_rsrc_t k_rsrc, v_rsrc;   // K and V of this head as raw buffers ending with token n-1
+    uint32_t k_voff[kLd], v_voff[kLd];       // byte offset of this lane's 16 bytes in tile 0
+    uint32_t ld_dst[kLd];                    // LDS offset of the 1024-byte block inside a K tile (wave-uniform)
+    uint32_t tile_bytes;                     // global byte distance between consecutive tiles
+    uint32_t k_lane[D / 16];                 // K tile offset of the MFMA operand for step kk (first round of a tile)
+    uint32_t v_lane[D / 32];                 // V tile offset of the first transposing read for block mb
+    int n, n_tiles, n_rounds, half;
+};
 
-    // ---- lazy running maximum: only act when some score is far above it
+// global -> LDS loads of one K/V tile into the stage at byte offset stage_off.  One
+// wave-wide instruction moves 1024 bytes (lane L fills bytes 16L..16L+15 of the block).
+// Rows past token n-1 lie outside the buffers and arrive as zeros.
+template <int D, int NB>
+__device__ __forceinline__ void issue_tile(unsigned char *smem, const Lane<D, NB> &c, int tile, uint32_t stage_off) {
+    using T = Tile<D, NB>;
+    const uint32_t soff = uint32_t(tile) * c.tile_bytes;
+#pragma unroll
+    for (int i = 0; i < Lane<D, NB>::kLd; ++i) {
+        // (operands go through plainly typed locals: the builtin is checked where it is written)
+        unsigned char *dst_k = smem + stage_off + c.ld_dst[i];
+        unsigned char *dst_v = dst_k + T::kTileBytes;
+        const uint32_t voff_k = c.k_voff[i], voff_v = c.v_voff[i];
+        const __amdgpu_buffer_rsrc_t rsrc_k = c.k_rsrc, rsrc_v = c.v_rsrc;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_k, LP_LDS_PTR(void, dst_k), 16, voff_k, soff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_v, LP_LDS_PTR(void, dst_v), 16, voff_v, soff, 0, 0);
+    }
+}
+
+// Keys past the end get score -inf.  Accumulator register i of a lane is key
+// 32*r + 16*(i/8) + 8*half + i%8.
+template <int NB>
+__device__ __forceinline__ void mask_scores(int r, int half, int n, f32x16 (&s)[NB]) {
+    const int kbase = r * 32 + half * 8;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (kbase + 16 * (i / 8) + (i % 8) >= n) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) s[nb][i] = -INFINITY;
+        }
+    }
+}
+
+// bf16 probabilities exp2(s - m) laid out as PV operands; the row sum adds the rounded values.
+template <int NB>
+__device__ __forceinline__ void probabilities(const f32x16 (&s)[NB], bf16x8 (&p)[NB][2], const float (&m_run)[NB],
+                                              float (&l_run)[NB]) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        Pack16 lo, hi;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        const float m = m_run[nb];
+        float l = l_run[nb];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][2 * e] - m), __builtin_amdgcn_exp2f(s[nb][2 * e + 1] - m));
+            hi.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][8 + 2 * e] - m), __builtin_amdgcn_exp2f(s[nb][8 + 2 * e + 1] - m));
+            l = __builtin_amdgcn_fdot2_f32_bf16(lo.p[e], ones, l, false);
+            l = __builtin_amdgcn_fdot2_f32_bf16(hi.p[e], ones, l, false);
+        }
+        l_run[nb] = l;
+        p[nb][0] = lo.v;
+        p[nb][1] = hi.v;
+    }
+}
+
+// Lazy running maximum.  s holds scores that will be exponentiated NEXT; if any of them
+// is more than kRescaleThreshold above the running maximum, raise the maximum and rescale
+// what was accumulated under the old one: the output accumulators, the row sums, and the
+// probabilities p_pending that have been computed but not yet multiplied into acc.
+template <int D, int NB>
+__device__ __forceinline__ void raise_maximum(const f32x16 (&s)[NB], bf16x8 (&p_pending)[NB][2],
+                                              f32x16 (&acc)[D / 32][NB], float (&m_run)[NB], float (&l_run)[NB]) {
     bool raise = false;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) raise = raise || (max16(s_cur[nb]) - m_run[nb] > kRescaleThreshold);
+    for (int nb = 0; nb < NB; ++nb) raise = raise || (max16(s[nb]) - m_run[nb] > kRescaleThreshold);
     if (__any(raise)) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            float tmax = max16(s_cur[nb]);
+            float tmax = max16(s[nb]);
             tmax = fmaxf(tmax, other_half(tmax));
             const float m_new = fmaxf(m_run[nb], tmax);      // the maximum never goes down
             const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
@@ -241,29 +198,127 @@ __device__ __forceinline__ void round_body(unsigned char *smem, const LaneCtx &c
             for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[mb][nb][i] *= alpha;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                Pack16 t;
+                t.v = p_pending[nb][ks];
+                const uint32_t w[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    t.p[e] = to_bf16x2(__uint_as_float(w[e] << 16) * alpha, __uint_as_float(w[e] & 0xffff0000u) * alpha);
+                p_pending[nb][ks] = t.v;
+            }
         }
+    }
+}
+
+// One K operand (16 bytes of a K row) from LDS: SUB selects the first or second round of
+// the tile whose operand addresses are k_addr.
+template <int D, int NB, int SUB>
+__device__ __forceinline__ bf16x8 load_k_operand(const uint32_t (&k_addr)[D / 16], int kk) {
+    return lds_load<bf16x8>(k_addr[kk] + SUB * 32 * Tile<D, NB>::kRowBytes);
+}
+
+// One V^T operand via two transposing reads.  Inside a group of 16 lanes, lane j supplies
+// the 8-byte chunk (row j/4, columns 4*(j%4)..+3) and receives column j of that 4x16 block,
+// i.e. 4 consecutive keys of one d.  Operand j covers keys 16*(j / MB).. of the round and
+// rows 32*(j % MB).. of O^T.
+template <int D, int NB, int SUB>
+__device__ __forceinline__ bf16x8 load_v_operand(const uint32_t (&v_addr)[D / 32], int j) {
+    using T = Tile<D, NB>;
+    constexpr int MB = D / 32;
+    const uint32_t a0 = v_addr[j % MB] + (SUB * 32 + (j / MB) * 16) * T::kRowBytes;
+    Pack16 a;
+    a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, uintptr_t(a0)));
+    a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, uintptr_t(a0 + 4 * T::kRowBytes)));
+    return a.v;
+}
+
+// Everything one wavefront carries from step to step.
+template <int D, int NB>
+struct Pipe {
+    bf16x8 qreg[NB][D / 16];       // Q^T operands (pre-scaled)
+    bf16x8 opreg[D / 16];          // LDS operands: K rows before a score product, V^T blocks before a PV product
+    f32x16 acc[D / 32][NB];        // O^T accumulators
+    float m_run[NB];               // running maximum (log2 units), common to both half-waves
+    float l_run[NB];               // this lane's share of the running sum
+    uint32_t k_addr[D / 16];       // LDS addresses of the K operands, tile of the next K fetch
+    uint32_t v_addr[D / 32];       // LDS addresses of the V operands, tile of the next V fetch
+    uint32_t tile_off;             // stage offset of tile i/2
+    uint32_t issue_off;            // stage offset the next issued tile goes to
+    int issue_t;                   // index of the next tile to issue
+};
+
+template <int BYTES>
+__device__ __forceinline__ uint32_t next_stage(uint32_t off) {
+    off += BYTES;
+    return off == kStages * BYTES ? 0u : off;
+}
+
+// Step i of the software pipeline (SUB = i % 2).  For ONE wavefront a step issues
+//   MFMA:  S^T of round i+1, then O^T += V^T P^T of round i-1
+//   VALU:  probabilities of round i, then the maximum check for round i+1
+//   LDS :  each score MFMA is followed by the fetch of a V operand of round i-1 into the
+//          registers it has just read, each PV MFMA by the fetch of a K operand of round i+2
+// so that matrix and vector work of the same wavefront overlap, an LDS operand is fetched
+// half a step before its product, and K and V operands share one set of registers.
+// Even steps open tile t+1 (t = i/2): they wait for its loads, pass the barrier (after which
+// every wave has fetched its last operand from tile t-2), and refill that stage with tile
+// t+kStages-2.  TAIL = false assumes i >= 1 and that rounds i+1 and i+2 exist (the steady
+// state, free of conditionals); TAIL = true checks.
+template <int D, int NB, int SUB, bool TAIL>
+__device__ __forceinline__ void pipeline_step(unsigned char *smem, uint32_t lds0, const Lane<D, NB> &c, int i,
+                                              Pipe<D, NB> &w, f32x16 (&s_cur)[NB], f32x16 (&s_nxt)[NB],
+                                              bf16x8 (&p_prev)[NB][2], bf16x8 (&p_cur)[NB][2]) {
+    using T = Tile<D, NB>;
+    constexpr int KS = D / 16, MB = D / 32;
+    const bool have_next = !TAIL || i + 1 < c.n_rounds;
+    const bool have_next2 = !TAIL || i + 2 < c.n_rounds;
+    const bool have_prev = !TAIL || i > 0;
+    if (SUB == 0) {
+        if (i > 0) w.tile_off = next_stage<T::kStageBytes>(w.tile_off);
+        if (have_next2) {
+            wait_tile_loads<0>();              // tile t+1, issued one tile ago
+            __syncthreads();
+            if (w.issue_t < c.n_tiles) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
+            ++w.issue_t;
+            w.issue_off = next_stage<T::kStageBytes>(w.issue_off);
+            const uint32_t nxt_off = next_stage<T::kStageBytes>(w.tile_off);
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) w.k_addr[kk] = lds0 + nxt_off + c.k_lane[kk];
+        }
+    } else {
+        // round i-1 is the first of tile i/2: the V fetches move on to that tile
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) w.v_addr[mb] = lds0 + w.tile_off + c.v_lane[mb];
     }
 
-    // ---- probabilities, rounded to bf16; the row sum adds the rounded values
-    bf16x8 p[NB][2];
+    f32x16 zero16;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        Pack16 lo, hi;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-        const float m = m_run[nb];
-        float l = l_run[nb];
+    for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            lo.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s_cur[nb][2 * e] - m), __builtin_amdgcn_exp2f(s_cur[nb][2 * e + 1] - m));
-            hi.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s_cur[nb][8 + 2 * e] - m), __builtin_amdgcn_exp2f(s_cur[nb][8 + 2 * e + 1] - m));
-            l = __builtin_amdgcn_fdot2_f32_bf16(lo.p[e], ones, l, false);
-            l = __builtin_amdgcn_fdot2_f32_bf16(hi.p[e], ones, l, false);
+    for (int j = 0; j < KS; ++j) {
+        if (have_next) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], w.qreg[nb][j], j == 0 ? zero16 : s_nxt[nb], 0, 0, 0);
         }
-        l_run[nb] = l;
-        p[nb][0] = lo.v;
-        p[nb][1] = hi.v;
+        if (have_prev) w.opreg[j] = load_v_operand<D, NB, 1 - SUB>(w.v_addr, j);
     }
-    pv_round<D, NB>(smem, c, r, p, acc);
+    probabilities<NB>(s_cur, p_cur, w.m_run, w.l_run);
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {
+        if (have_prev) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], p_prev[nb][j / MB], w.acc[j % MB][nb], 0, 0, 0);
+        }
+        if (have_next2) w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
+    }
+    if (have_next) {
+        if (TAIL && (i + 2) * 32 > c.n) mask_scores<NB>(i + 1, c.half, c.n, s_nxt);
+        raise_maximum<D, NB>(s_nxt, p_cur, w.acc, w.m_run, w.l_run);
+    }
 }
 
 template <int D, int NB>
@@ -272,9 +327,11 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
     __bf16 *__restrict__ o, int n, int heads, int64_t stride_tok, int64_t stride_head,
     float scale_log2e, int n_qtiles) {
     using T = Tile<D, NB>;
+    using L = Lane<D, NB>;
     constexpr int KS = D / 16;        // MFMA steps along d for S^T
     constexpr int MB = D / 32;        // 32-row blocks of O^T
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const uint32_t lds0 = uint32_t(uintptr_t(LP_LDS_PTR(unsigned char, smem)));
 
     // Workgroup -> (head, query tile).  Consecutive workgroup ids are dealt round
     // robin to the 8 XCDs; remap so each XCD works on a contiguous range of
@@ -288,35 +345,65 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
     const int qtile = logical % n_qtiles;
 
     const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const int lane = tid % 64;
     const int col = lane % 32;        // MFMA column (query) / A-operand row
+    const int half = lane / 32;
     const int64_t head_off = int64_t(head) * stride_head;
     const __bf16 *qh = q + head_off;
     __bf16 *oh = o + head_off;
 
-    LaneCtx c;
-    c.kh = k + head_off;
-    c.vh = v + head_off;
-    c.stride_tok = stride_tok;
+    L c;
     c.n = n;
     c.n_tiles = (n + kBN - 1) / kBN;
     c.n_rounds = (n + 31) / 32;
-    c.wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    c.half = lane / 32;
-    c.krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
-    c.vj = lane % 16;
-    c.vg = (lane / 16) % 2;
-    c.ld_row = lane / T::kGran;
-    c.ld_gran = lane % T::kGran;
-
+    c.half = half;
+    {
+        // raw buffers over this head's K and V, ending with the last element of token n-1
+        // (flags: 32-bit data format, as every untyped buffer on this architecture)
+        const int valid_bytes = int((int64_t(n - 1) * stride_tok + D) * 2);
+        c.k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(k + head_off), 0, valid_bytes, 0x00020000);
+        c.v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(v + head_off), 0, valid_bytes, 0x00020000);
+        c.tile_bytes = uint32_t(kBN * stride_tok * 2);
+    }
 #pragma unroll
-    for (int t = 0; t < kStages - 1; ++t)
-        if (t < c.n_tiles) issue_tile<D, NB>(smem, c, t);
+    for (int i = 0; i < L::kLd; ++i) {
+        const int instr = wave + i * T::kWaves;
+        const int row = instr * T::kRowsPerInstr + lane / T::kGran;
+        const int gran = lane % T::kGran;          // physical granule this lane fills
+        c.ld_dst[i] = instr * 1024;
+        c.k_voff[i] = uint32_t(row * stride_tok * 2) + 16 * (gran ^ T::swz_k(row));
+        c.v_voff[i] = uint32_t(row * stride_tok * 2) + 16 * (gran ^ T::swz_v(row));
+    }
+    {
+        // K operand: row = col with bits 2 and 3 swapped, so that accumulator register i
+        // of a lane is key 16*(i/8) + 8*half + i%8 of the round
+        const int krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+            c.k_lane[kk] = krow * T::kRowBytes + 16 * ((2 * kk + half) ^ T::swz_k(krow));
+        const int vj = lane % 16, vg = (lane / 16) % 2;
+        const int vrow = half * 8 + vj / 4;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            c.v_lane[mb] = T::kTileBytes + vrow * T::kRowBytes + 8 * ((vj % 4) % 2) +
+                           16 * ((4 * mb + 2 * vg + (vj % 4) / 2) ^ T::swz_v(vrow));
+    }
+
+    // stage s lives at byte offset s * kStageBytes; tile t uses stage t % kStages
+    Pipe<D, NB> w;
+    w.issue_off = 0;
+    w.issue_t = 0;
+#pragma unroll
+    for (int t = 0; t < kStages - 2; ++t) {
+        if (t < c.n_tiles) issue_tile<D, NB>(smem, c, t, w.issue_off);
+        w.issue_off += T::kStageBytes;
+        ++w.issue_t;
+    }
 
     // ---- Q^T operands, pre-multiplied by scale*log2(e): lane holds, for query `col`
     // of block nb, d = 16*kk + 8*half .. +7
-    const int q0 = qtile * kBM + c.wave * (32 * NB);
-    bf16x8 qreg[NB][KS];
+    const int q0 = qtile * kBM + wave * (32 * NB);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int qi = q0 + nb * 32 + col;
@@ -324,50 +411,92 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
         for (int kk = 0; kk < KS; ++kk) {
             Pack16 t;
             t.u = make_uint4(0, 0, 0, 0);
-            if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + c.half * 8);
-            const uint32_t w[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
+            if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + half * 8);
+            const uint32_t u[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)   // a bf16 is the upper half of the binary32 with the same value
-                t.p[e] = to_bf16x2(__uint_as_float(w[e] << 16) * scale_log2e, __uint_as_float(w[e] & 0xffff0000u) * scale_log2e);
-            qreg[nb][kk] = t.v;
+                t.p[e] = to_bf16x2(__uint_as_float(u[e] << 16) * scale_log2e, __uint_as_float(u[e] & 0xffff0000u) * scale_log2e);
+            w.qreg[nb][kk] = t.v;
         }
     }
-
-    f32x16 acc[MB][NB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.0f;
-    float m_run[NB];                  // running maximum (log2 units), common to both half-waves
-    float l_run[NB];                  // this lane's share of the running sum
+            for (int r = 0; r < 16; ++r) w.acc[mb][nb][r] = 0.0f;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) l_run[nb] = 0.0f;
+    for (int nb = 0; nb < NB; ++nb) w.l_run[nb] = 0.0f;
 
     // ---- round 0 fixes the initial maximum
     wait_tile_loads<0>();
     __syncthreads();
+    w.tile_off = 0;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) w.k_addr[kk] = lds0 + c.k_lane[kk];
     f32x16 s_a[NB], s_b[NB];
-    score_round<D, NB>(smem, c, 0, qreg, s_a);
-    if (n < 32) mask_round<NB>(c, 0, s_a);
+    bf16x8 p_a[NB][2], p_b[NB][2];
+    {
+        f32x16 zero16;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) w.opreg[kk] = load_k_operand<D, NB, 0>(w.k_addr, kk);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                s_a[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[kk], w.qreg[nb][kk], kk == 0 ? zero16 : s_a[nb], 0, 0, 0);
+        if (c.n_rounds > 1) {
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) w.opreg[kk] = load_k_operand<D, NB, 1>(w.k_addr, kk);
+        }
+    }
+    if (n < 32) mask_scores<NB>(0, half, n, s_a);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const float tmax = max16(s_a[nb]);
-        m_run[nb] = fmaxf(tmax, other_half(tmax));
+        w.m_run[nb] = fmaxf(tmax, other_half(tmax));
         s_b[nb] = s_a[nb];
+        p_b[nb][0] = w.qreg[nb][0];     // defined values; never used before being written
+        p_b[nb][1] = w.qreg[nb][0];
     }
 
-    for (int r = 0; r < c.n_rounds; r += 2) {
-        round_body<D, NB>(smem, c, r, qreg, s_a, s_b, acc, m_run, l_run);
-        if (r + 1 < c.n_rounds) round_body<D, NB>(smem, c, r + 1, qreg, s_b, s_a, acc, m_run, l_run);
+    // ---- the pipeline: step 0 (no PV yet), the steady state two steps at a time, the
+    // last steps with their conditions, and the PV product of the last round
+    pipeline_step<D, NB, 0, true>(smem, lds0, c, 0, w, s_a, s_b, p_b, p_a);
+    int i = 1;
+    for (; i + 3 < c.n_rounds; i += 2) {
+        pipeline_step<D, NB, 1, false>(smem, lds0, c, i, w, s_b, s_a, p_a, p_b);
+        pipeline_step<D, NB, 0, false>(smem, lds0, c, i + 1, w, s_a, s_b, p_b, p_a);
+    }
+    for (; i < c.n_rounds; ++i) {
+        if (i & 1)
+            pipeline_step<D, NB, 1, true>(smem, lds0, c, i, w, s_b, s_a, p_a, p_b);
+        else
+            pipeline_step<D, NB, 0, true>(smem, lds0, c, i, w, s_a, s_b, p_b, p_a);
+    }
+    {
+        // PV product of the last round: its V operands still have to be fetched
+        const int last = c.n_rounds - 1;     // (w.tile_off already is the stage of tile last/2)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) w.v_addr[mb] = lds0 + w.tile_off + c.v_lane[mb];
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            const bf16x8 a = (last & 1) ? load_v_operand<D, NB, 1>(w.v_addr, j) : load_v_operand<D, NB, 0>(w.v_addr, j);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const bf16x8 pj = (last & 1) ? p_b[nb][j / MB] : p_a[nb][j / MB];
+                w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pj, w.acc[j % MB][nb], 0, 0, 0);
+            }
+        }
     }
 
     // ---- normalise and store: lane holds, for query `col` of block nb, rows
     // d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const float l_tot = l_run[nb] + other_half(l_run[nb]);
+        const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
         const float inv = 1.0f / l_tot;
         const int qi = q0 + nb * 32 + col;
         if (qi < n) {
@@ -376,10 +505,10 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
             for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    union { uint2 u; bf16x2 p[2]; } w;
-                    w.p[0] = to_bf16x2(acc[mb][nb][4 * g + 0] * inv, acc[mb][nb][4 * g + 1] * inv);
-                    w.p[1] = to_bf16x2(acc[mb][nb][4 * g + 2] * inv, acc[mb][nb][4 * g + 3] * inv);
-                    *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + c.half * 4) = w.u;
+                    union { uint2 u; bf16x2 p[2]; } ow;
+                    ow.p[0] = to_bf16x2(w.acc[mb][nb][4 * g + 0] * inv, w.acc[mb][nb][4 * g + 1] * inv);
+                    ow.p[1] = to_bf16x2(w.acc[mb][nb][4 * g + 2] * inv, w.acc[mb][nb][4 * g + 3] * inv);
+                    *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + half * 4) = ow.u;
                 }
         }
     }
