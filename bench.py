@@ -77,6 +77,8 @@ def main() -> int:
             dev = [torch.from_numpy(a.view(np.int16)).cuda() for a in host]
             qkv.append((n, dev[0], dev[1], dev[2], torch.empty_like(dev[0])))
         state[dim] = dict(plan=plan, parts=parts, subs=subs, preds=preds, qkv=qkv)
+    ws_bytes = lp.lp_attention_workspace_size(w.head_dim)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
 
     def flops_of(n):
@@ -99,7 +101,7 @@ def main() -> int:
             n, qd, kd, vd, od = item
             for _ in range(layers):
                 a0 = ev(); a0.record()
-                lp.lp_attention(qd, kd, vd, od, n, w.heads, w.head_dim, w.heads * w.head_dim, w.head_dim, 0.0, stream)
+                lp.lp_attention(qd, kd, vd, od, n, w.heads, w.head_dim, w.heads * w.head_dim, w.head_dim, 0.0, ws, ws_bytes, stream)
                 a1 = ev(); a1.record()
                 att.append((a0, a1, n))
         e2 = ev(); e2.record()

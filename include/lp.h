@@ -123,21 +123,42 @@ int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, v
 /*
  * Self-attention inside one sub-latent: for every head h and token i,
  *   o[i,h,:] = sum_j softmax_j(scale * <q[i,h,:], k[j,h,:]>) v[j,h,:]
- * over all n_tokens tokens j of the sub-latent (no mask, not causal).
+ * over all n_tokens tokens j of the sub-latent (no mask, not causal): inside a
+ * sub-latent the DiT blocks attend globally over all of its positions
+ * (supplement, proof of Theorem 1, step 3).
  * q, k, v, o: device, bfloat16; element (token, head, d) lives at
  * token * stride_tok + head * stride_head + d (strides in elements, the same
- * for all four tensors; d contiguous).  Required: head_dim in {64, 128},
- * stride_head >= head_dim, stride_tok >= heads * ... such that rows do not
- * overlap, both strides multiples of 8 and all four base pointers 16-byte
- * aligned (else LP_ERR_INVALID_ARG).  o must not alias q, k or v.
+ * for all four tensors; d contiguous).  Required: head_dim in {64, 128}; both
+ * strides multiples of 8 and all four base pointers 16-byte aligned; rows must
+ * not overlap, i.e. either stride_tok >= heads * stride_head >= heads * head_dim
+ * (token-major) or stride_head >= n_tokens * stride_tok, stride_tok >= head_dim
+ * (head-major); (n_tokens * stride_tok + head_dim) * 2 < 2^31 (else
+ * LP_ERR_UNSUPPORTED).  o must not alias q, k or v.
  * scale <= 0 selects 1/sqrt(head_dim).  n_tokens = 0 is a successful no-op.
- * Products run on bf16 MFMA with binary32 accumulation; the softmax is
- * binary32; probabilities are rounded to bf16 before the second product and
- * the result is rounded to bf16 on store.
+ * workspace: optional device scratch of at least
+ * lp_attention_workspace_size(head_dim) bytes, 16-byte aligned, contents
+ * irrelevant on entry and undefined on return.  With it the work is dealt evenly
+ * over the compute units whatever n_tokens and heads are (partial results of a
+ * query tile that two workgroups share pass through the workspace and a second
+ * small kernel merges them); with NULL (or too small a workspace) one workgroup
+ * is launched per 256-row query tile and head, which leaves compute units idle
+ * when their number does not divide the tile count.  Two calls that overlap in
+ * time must not share a workspace.
+ * Products run on bf16 MFMA with binary32 accumulation; q is multiplied by
+ * scale*log2(e) and re-rounded to bf16 once; the softmax is binary32;
+ * probabilities are rounded to bf16 before the second product and the result is
+ * rounded to bf16 on store.
  */
 int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
                  int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
-                 float scale, void *stream);
+                 float scale, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * Bytes of workspace lp_attention can use on the current device for this
+ * head_dim (2 partial-result slots per compute unit; about 68 MB for head_dim
+ * 128 on 256 compute units).  Negative LP_ERR_* on failure.
+ */
+int64_t lp_attention_workspace_size(int32_t head_dim);
 
 const char *lp_strerror(int status); /* static string, never NULL              */
 int lp_last_hip_error(void);         /* hipError_t of the last LP_ERR_HIP (thread local) */

@@ -31,7 +31,7 @@ LP_MAX_PARTS = 64
 EXPORTS = (
     "lp_rotation_dim", "lp_plan_create", "lp_plan_destroy", "lp_plan_num_parts", "lp_plan_dim",
     "lp_plan_total_elems", "lp_plan_latent_elems", "lp_plan_query", "lp_partition", "lp_reconstruct",
-    "lp_attention", "lp_strerror", "lp_last_hip_error", "lp_version",
+    "lp_attention", "lp_attention_workspace_size", "lp_strerror", "lp_last_hip_error", "lp_version",
 )
 
 
@@ -93,8 +93,10 @@ def _lib():
         lib.lp_partition.restype = C.c_int
         lib.lp_reconstruct.argtypes = [vp, vp, vp, vp]
         lib.lp_reconstruct.restype = C.c_int
-        lib.lp_attention.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i64, C.c_float, vp]
+        lib.lp_attention.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i64, C.c_float, vp, i64, vp]
         lib.lp_attention.restype = C.c_int
+        lib.lp_attention_workspace_size.argtypes = [i32]
+        lib.lp_attention_workspace_size.restype = i64
         lib.lp_strerror.argtypes = [C.c_int]
         lib.lp_strerror.restype = C.c_char_p
         lib.lp_last_hip_error.argtypes = []
@@ -211,7 +213,15 @@ def lp_reconstruct(plan: Plan, preds_packed, out, stream: Optional[int] = None) 
     _check(_lib().lp_reconstruct(plan.handle, _ptr(preds_packed), _ptr(out), stream or None), "lp_reconstruct")
 
 
+def lp_attention_workspace_size(head_dim: int) -> int:
+    n = int(_lib().lp_attention_workspace_size(int(head_dim)))
+    if n < 0:
+        raise LPError(n, "lp_attention_workspace_size")
+    return n
+
+
 def lp_attention(q, k, v, o, n_tokens: int, heads: int, head_dim: int, stride_tok: int, stride_head: int,
-                 scale: float = 0.0, stream: Optional[int] = None) -> None:
+                 scale: float = 0.0, workspace=None, workspace_bytes: int = 0, stream: Optional[int] = None) -> None:
     _check(_lib().lp_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(o), int(n_tokens), int(heads), int(head_dim),
-                               int(stride_tok), int(stride_head), float(scale), stream or None), "lp_attention")
+                               int(stride_tok), int(stride_head), float(scale), _ptr(workspace) or None,
+                               int(workspace_bytes), stream or None), "lp_attention")

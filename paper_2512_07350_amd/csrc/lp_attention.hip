@@ -104,8 +104,7 @@ __device__ __forceinline__ float max16(const f32x16 &s) {
     return t;
 }
 
-// What a lane needs to know to move and read tiles; everything here is fixed for the
-// whole kernel.
+// What a lane needs to know to move tiles from global memory into LDS.
 template <int D, int NB>
 struct Lane {
     using T = Tile<D, NB>;
@@ -114,9 +113,9 @@ struct Lane {
     uint32_t k_voff[kLd], v_voff[kLd];       // byte offset of this lane's 16 bytes in tile 0
     uint32_t ld_dst[kLd];                    // LDS offset of the 1024-byte block inside a K tile (wave-uniform)
     uint32_t tile_bytes;                     // global byte distance between consecutive tiles
-    uint32_t k_lane[D / 16];                 // K tile offset of the MFMA operand for step kk (first round of a tile)
-    uint32_t v_lane[D / 32];                 // V tile offset of the first transposing read for block mb
-    int n, n_tiles, n_rounds, half;
+    int half;                                // lane / 32
+    int key_end;                             // keys at and past this index do not exist for the current segment
+    int t_end;                               // one past the segment's last tile
 };
 
 // global -> LDS loads of one K/V tile into the stage at byte offset stage_off.  One
@@ -242,8 +241,9 @@ struct Pipe {
     f32x16 acc[D / 32][NB];        // O^T accumulators
     float m_run[NB];               // running maximum (log2 units), common to both half-waves
     float l_run[NB];               // this lane's share of the running sum
-    uint32_t k_addr[D / 16];       // LDS addresses of the K operands, tile of the next K fetch
-    uint32_t v_addr[D / 32];       // LDS addresses of the V operands, tile of the next V fetch
+    uint32_t k_addr[D / 16];       // LDS addresses of the K operands in the stage at k_off
+    uint32_t v_addr[D / 32];       // LDS addresses of the V operands in the stage at v_off
+    uint32_t k_off, v_off;         // stage offsets k_addr / v_addr currently point into
     uint32_t tile_off;             // stage offset of tile i/2
     uint32_t issue_off;            // stage offset the next issued tile goes to
     int issue_t;                   // index of the next tile to issue
@@ -264,33 +264,38 @@ __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
 // half a step before its product, and K and V operands share one set of registers.
 // Even steps open tile t+1 (t = i/2): they wait for its loads, pass the barrier (after which
 // every wave has fetched its last operand from tile t-2), and refill that stage with tile
-// t+kStages-2.  TAIL = false assumes i >= 1 and that rounds i+1 and i+2 exist (the steady
-// state, free of conditionals); TAIL = true checks.
-template <int D, int NB, int SUB, bool TAIL>
-__device__ __forceinline__ void pipeline_step(unsigned char *smem, uint32_t lds0, const Lane<D, NB> &c, int i,
+// t+kStages-2.
+// The same code runs at the ends of a segment: rounds that do not exist get scores -inf
+// (probabilities 0) and the round before the first has probabilities 0, so the products
+// issued for them add nothing; their operands are read from valid, if stale, LDS addresses.
+template <int D, int NB, int SUB>
+__device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D, NB> &c, int i, bool first,
                                               Pipe<D, NB> &w, f32x16 (&s_cur)[NB], f32x16 (&s_nxt)[NB],
                                               bf16x8 (&p_prev)[NB][2], bf16x8 (&p_cur)[NB][2]) {
     using T = Tile<D, NB>;
     constexpr int KS = D / 16, MB = D / 32;
-    const bool have_next = !TAIL || i + 1 < c.n_rounds;
-    const bool have_next2 = !TAIL || i + 2 < c.n_rounds;
-    const bool have_prev = !TAIL || i > 0;
     if (SUB == 0) {
-        if (i > 0) w.tile_off = next_stage<T::kStageBytes>(w.tile_off);
-        if (have_next2) {
-            wait_tile_loads<0>();              // tile t+1, issued one tile ago
-            __syncthreads();
-            if (w.issue_t < c.n_tiles) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
-            ++w.issue_t;
-            w.issue_off = next_stage<T::kStageBytes>(w.issue_off);
-            const uint32_t nxt_off = next_stage<T::kStageBytes>(w.tile_off);
+        if (!first) w.tile_off = next_stage<T::kStageBytes>(w.tile_off);
+        wait_tile_loads<0>();              // tile t+1, issued one tile ago
+        __syncthreads();
+        if (w.issue_t < c.t_end) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
+        ++w.issue_t;
+        w.issue_off = next_stage<T::kStageBytes>(w.issue_off);
+        const uint32_t nxt_off = next_stage<T::kStageBytes>(w.tile_off);
+        const uint32_t delta = nxt_off - w.k_off;       // wraps; the sum below does not
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) w.k_addr[kk] = lds0 + nxt_off + c.k_lane[kk];
-        }
+        for (int kk = 0; kk < KS; ++kk) w.k_addr[kk] += delta;
+        w.k_off = nxt_off;
     } else {
-        // round i-1 is the first of tile i/2: the V fetches move on to that tile
+        // round i-1 is the first of tile i/2: the V fetches move on to that tile -- unless it
+        // lies past the segment and was never loaded (its probabilities are 0, and 0 times
+        // whatever an unwritten stage holds need not be 0)
+        if (i / 2 < c.t_end) {
+            const uint32_t delta = w.tile_off - w.v_off;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) w.v_addr[mb] = lds0 + w.tile_off + c.v_lane[mb];
+            for (int mb = 0; mb < MB; ++mb) w.v_addr[mb] += delta;
+            w.v_off = w.tile_off;
+        }
     }
 
     f32x16 zero16;
@@ -298,34 +303,58 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, uint32_t lds0
     for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
-        if (have_next) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], w.qreg[nb][j], j == 0 ? zero16 : s_nxt[nb], 0, 0, 0);
-        }
-        if (have_prev) w.opreg[j] = load_v_operand<D, NB, 1 - SUB>(w.v_addr, j);
+        for (int nb = 0; nb < NB; ++nb)
+            s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], w.qreg[nb][j], j == 0 ? zero16 : s_nxt[nb], 0, 0, 0);
+        w.opreg[j] = load_v_operand<D, NB, 1 - SUB>(w.v_addr, j);
     }
     probabilities<NB>(s_cur, p_cur, w.m_run, w.l_run);
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
-        if (have_prev) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], p_prev[nb][j / MB], w.acc[j % MB][nb], 0, 0, 0);
-        }
-        if (have_next2) w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
+        for (int nb = 0; nb < NB; ++nb)
+            w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], p_prev[nb][j / MB], w.acc[j % MB][nb], 0, 0, 0);
+        w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
     }
-    if (have_next) {
-        if (TAIL && (i + 2) * 32 > c.n) mask_scores<NB>(i + 1, c.half, c.n, s_nxt);
-        raise_maximum<D, NB>(s_nxt, p_cur, w.acc, w.m_run, w.l_run);
-    }
+    if ((i + 2) * 32 > c.key_end) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
+    raise_maximum<D, NB>(s_nxt, p_cur, w.acc, w.m_run, w.l_run);
+}
+
+// Launch parameters.  The iteration space is (unit, key tile): a unit is one 256-row query
+// tile of one head, and every unit walks tiles_per_unit tiles of 64 keys.  The grid's
+// workgroups cut that space into equal contiguous ranges, so a workgroup may start and end
+// in the middle of a unit; such partial results go to `ws` and are merged by
+// combine_kernel.  With one workgroup per unit nothing is partial.
+struct AttnParams {
+    const __bf16 *q, *k, *v;
+    __bf16 *o;
+    float *ws;                 // slots for partial results: 2 per workgroup
+    int64_t stride_tok, stride_head;
+    float scale_log2e;
+    int n, n_qtiles, tiles_per_unit, n_units;
+    uint32_t total_work;       // n_units * tiles_per_unit
+};
+
+// A slot holds, for the 256 query rows of a unit: m[256], l[256], then the unnormalised
+// O rows [256][D], all binary32.
+template <int D>
+constexpr int slot_floats() { return kBM * (D + 2); }
+
+// First iteration of (logical) workgroup p when W iterations are dealt to P workgroups.
+__device__ __forceinline__ uint32_t range_start(uint32_t p, uint32_t W, uint32_t P) {
+    return uint32_t(uint64_t(p) * W / P);
+}
+
+// Workgroup ids are dealt round robin to the 8 XCDs; remap so that each XCD owns a
+// contiguous stretch of the iteration space and the K/V of a head stay in one XCD's L2.
+__device__ __forceinline__ uint32_t logical_workgroup(uint32_t b, uint32_t n_wg) {
+    const uint32_t xcd = b % 8, slot = b / 8;
+    const uint32_t base = n_wg / 8, rem = n_wg % 8;
+    return xcd * base + (xcd < rem ? xcd : rem) + slot;
 }
 
 template <int D, int NB>
-__global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
-    const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
-    __bf16 *__restrict__ o, int n, int heads, int64_t stride_tok, int64_t stride_head,
-    float scale_log2e, int n_qtiles) {
+__global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const AttnParams a) {
     using T = Tile<D, NB>;
     using L = Lane<D, NB>;
     constexpr int KS = D / 16;        // MFMA steps along d for S^T
@@ -333,39 +362,19 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const uint32_t lds0 = uint32_t(uintptr_t(LP_LDS_PTR(unsigned char, smem)));
 
-    // Workgroup -> (head, query tile).  Consecutive workgroup ids are dealt round
-    // robin to the 8 XCDs; remap so each XCD works on a contiguous range of
-    // (head, tile) pairs and the K/V of a head stay in one XCD's L2.
-    const uint32_t n_wg = gridDim.x;
-    const uint32_t b = blockIdx.x;
-    const uint32_t xcd = b % 8, slot = b / 8;
-    const uint32_t base = n_wg / 8, rem = n_wg % 8;
-    const uint32_t logical = xcd * base + (xcd < rem ? xcd : rem) + slot;
-    const int head = logical / n_qtiles;
-    const int qtile = logical % n_qtiles;
-
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const int lane = tid % 64;
     const int col = lane % 32;        // MFMA column (query) / A-operand row
     const int half = lane / 32;
-    const int64_t head_off = int64_t(head) * stride_head;
-    const __bf16 *qh = q + head_off;
-    __bf16 *oh = o + head_off;
+    const int n = a.n;
+    const int64_t stride_tok = a.stride_tok;
+    const int n_rounds = (n + 31) / 32;
 
+    // ---- lane constants of the tile traffic
     L c;
-    c.n = n;
-    c.n_tiles = (n + kBN - 1) / kBN;
-    c.n_rounds = (n + 31) / 32;
     c.half = half;
-    {
-        // raw buffers over this head's K and V, ending with the last element of token n-1
-        // (flags: 32-bit data format, as every untyped buffer on this architecture)
-        const int valid_bytes = int((int64_t(n - 1) * stride_tok + D) * 2);
-        c.k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(k + head_off), 0, valid_bytes, 0x00020000);
-        c.v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(v + head_off), 0, valid_bytes, 0x00020000);
-        c.tile_bytes = uint32_t(kBN * stride_tok * 2);
-    }
+    c.tile_bytes = uint32_t(kBN * stride_tok * 2);
 #pragma unroll
     for (int i = 0; i < L::kLd; ++i) {
         const int instr = wave + i * T::kWaves;
@@ -375,190 +384,333 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(
         c.k_voff[i] = uint32_t(row * stride_tok * 2) + 16 * (gran ^ T::swz_k(row));
         c.v_voff[i] = uint32_t(row * stride_tok * 2) + 16 * (gran ^ T::swz_v(row));
     }
-    {
-        // K operand: row = col with bits 2 and 3 swapped, so that accumulator register i
-        // of a lane is key 16*(i/8) + 8*half + i%8 of the round
-        const int krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
+
+    // ---- this workgroup's range of the (unit, tile) iteration space
+    const uint32_t lp = logical_workgroup(blockIdx.x, gridDim.x);
+    uint32_t it = range_start(lp, a.total_work, gridDim.x);
+    const uint32_t it_end = range_start(lp + 1, a.total_work, gridDim.x);
+    const uint32_t tpu = uint32_t(a.tiles_per_unit);
+    bool first_segment = true;
+
+    while (it < it_end) {
+        const uint32_t unit = it / tpu;
+        const int t_begin = int(it - unit * tpu);
+        const int t_stop = int(min(tpu, uint32_t(t_begin) + (it_end - it)));
+        const int head = int(unit) / a.n_qtiles;
+        const int qtile = int(unit) % a.n_qtiles;
+        const int64_t head_off = int64_t(head) * a.stride_head;
+        const __bf16 *qh = a.q + head_off;
+
+        const int i_begin = 2 * t_begin;                 // rounds [i_begin, i_end) of 32 keys
+        const int i_end = min(2 * t_stop, n_rounds);
+        c.key_end = min(n, t_stop * kBN);
+        c.t_end = t_stop;
+        {
+            // raw buffers over this head's K and V, ending with the last element of token n-1
+            // (flags: 32-bit data format, as every untyped buffer on this architecture)
+            const int valid_bytes = int((int64_t(n - 1) * stride_tok + D) * 2);
+            c.k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(a.k + head_off), 0, valid_bytes, 0x00020000);
+            c.v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(a.v + head_off), 0, valid_bytes, 0x00020000);
+        }
+
+        // every wave has left the previous segment's tiles before their stages are refilled
+        __syncthreads();
+
+        // stage s lives at byte offset s * kStageBytes; the segment's tiles use the stages in turn
+        Pipe<D, NB> w;
+        w.issue_off = 0;
+        w.issue_t = t_begin;
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-            c.k_lane[kk] = krow * T::kRowBytes + 16 * ((2 * kk + half) ^ T::swz_k(krow));
-        const int vj = lane % 16, vg = (lane / 16) % 2;
-        const int vrow = half * 8 + vj / 4;
+        for (int t = 0; t < kStages - 2; ++t) {
+            if (w.issue_t < c.t_end) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
+            w.issue_off += T::kStageBytes;
+            ++w.issue_t;
+        }
+
+        // ---- Q^T operands, pre-multiplied by scale*log2(e): lane holds, for query `col`
+        // of block nb, d = 16*kk + 8*half .. +7
+        const int q0 = qtile * kBM + wave * (32 * NB);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int qi = q0 + nb * 32 + col;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+                Pack16 t;
+                t.u = make_uint4(0, 0, 0, 0);
+                if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + half * 8);
+                const uint32_t u[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)   // a bf16 is the upper half of the binary32 with the same value
+                    t.p[e] = to_bf16x2(__uint_as_float(u[e] << 16) * a.scale_log2e,
+                                       __uint_as_float(u[e] & 0xffff0000u) * a.scale_log2e);
+                w.qreg[nb][kk] = t.v;
+            }
+        }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            c.v_lane[mb] = T::kTileBytes + vrow * T::kRowBytes + 8 * ((vj % 4) % 2) +
-                           16 * ((4 * mb + 2 * vg + (vj % 4) / 2) ^ T::swz_v(vrow));
-    }
-
-    // stage s lives at byte offset s * kStageBytes; tile t uses stage t % kStages
-    Pipe<D, NB> w;
-    w.issue_off = 0;
-    w.issue_t = 0;
-#pragma unroll
-    for (int t = 0; t < kStages - 2; ++t) {
-        if (t < c.n_tiles) issue_tile<D, NB>(smem, c, t, w.issue_off);
-        w.issue_off += T::kStageBytes;
-        ++w.issue_t;
-    }
-
-    // ---- Q^T operands, pre-multiplied by scale*log2(e): lane holds, for query `col`
-    // of block nb, d = 16*kk + 8*half .. +7
-    const int q0 = qtile * kBM + wave * (32 * NB);
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int qi = q0 + nb * 32 + col;
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-            Pack16 t;
-            t.u = make_uint4(0, 0, 0, 0);
-            if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + half * 8);
-            const uint32_t u[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e)   // a bf16 is the upper half of the binary32 with the same value
-                t.p[e] = to_bf16x2(__uint_as_float(u[e] << 16) * scale_log2e, __uint_as_float(u[e] & 0xffff0000u) * scale_log2e);
-            w.qreg[nb][kk] = t.v;
-        }
-    }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) w.acc[mb][nb][r] = 0.0f;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) w.l_run[nb] = 0.0f;
-
-    // ---- round 0 fixes the initial maximum
-    wait_tile_loads<0>();
-    __syncthreads();
-    w.tile_off = 0;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) w.k_addr[kk] = lds0 + c.k_lane[kk];
-    f32x16 s_a[NB], s_b[NB];
-    bf16x8 p_a[NB][2], p_b[NB][2];
-    {
-        f32x16 zero16;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) w.opreg[kk] = load_k_operand<D, NB, 0>(w.k_addr, kk);
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                s_a[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[kk], w.qreg[nb][kk], kk == 0 ? zero16 : s_a[nb], 0, 0, 0);
-        if (c.n_rounds > 1) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) w.acc[mb][nb][r] = 0.0f;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) w.l_run[nb] = 0.0f;
+
+        // ---- LDS operand addresses in stage 0
+        w.tile_off = 0;
+        w.k_off = 0;
+        w.v_off = 0;
+        {
+            // K operand: row = col with bits 2 and 3 swapped, so that accumulator register i
+            // of a lane is key 16*(i/8) + 8*half + i%8 of the round
+            const int krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                w.k_addr[kk] = lds0 + krow * T::kRowBytes + 16 * ((2 * kk + half) ^ T::swz_k(krow));
+            const int vj = lane % 16, vg = (lane / 16) % 2;
+            const int vrow = half * 8 + vj / 4;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                w.v_addr[mb] = lds0 + T::kTileBytes + vrow * T::kRowBytes + 8 * ((vj % 4) % 2) +
+                               16 * ((4 * mb + 2 * vg + (vj % 4) / 2) ^ T::swz_v(vrow));
+        }
+
+        // ---- the segment's first round fixes the initial maximum
+        wait_tile_loads<0>();
+        __syncthreads();
+        f32x16 s_a[NB], s_b[NB];
+        bf16x8 p_a[NB][2], p_b[NB][2];
+        {
+            f32x16 zero16;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) w.opreg[kk] = load_k_operand<D, NB, 0>(w.k_addr, kk);
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    s_a[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[kk], w.qreg[nb][kk], kk == 0 ? zero16 : s_a[nb], 0, 0, 0);
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) w.opreg[kk] = load_k_operand<D, NB, 1>(w.k_addr, kk);
         }
-    }
-    if (n < 32) mask_scores<NB>(0, half, n, s_a);
+        if ((i_begin + 1) * 32 > c.key_end) mask_scores<NB>(i_begin, half, c.key_end, s_a);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const float tmax = max16(s_a[nb]);
-        w.m_run[nb] = fmaxf(tmax, other_half(tmax));
-        s_b[nb] = s_a[nb];
-        p_b[nb][0] = w.qreg[nb][0];     // defined values; never used before being written
-        p_b[nb][1] = w.qreg[nb][0];
-    }
+        for (int nb = 0; nb < NB; ++nb) {
+            const float tmax = max16(s_a[nb]);
+            w.m_run[nb] = fmaxf(tmax, other_half(tmax));
+            s_b[nb] = s_a[nb];
+            Pack16 z;
+            z.u = make_uint4(0, 0, 0, 0);
+            p_b[nb][0] = z.v;               // probabilities of the round before the first: none
+            p_b[nb][1] = z.v;
+        }
 
-    // ---- the pipeline: step 0 (no PV yet), the steady state two steps at a time, the
-    // last steps with their conditions, and the PV product of the last round
-    pipeline_step<D, NB, 0, true>(smem, lds0, c, 0, w, s_a, s_b, p_b, p_a);
-    int i = 1;
-    for (; i + 3 < c.n_rounds; i += 2) {
-        pipeline_step<D, NB, 1, false>(smem, lds0, c, i, w, s_b, s_a, p_a, p_b);
-        pipeline_step<D, NB, 0, false>(smem, lds0, c, i + 1, w, s_a, s_b, p_b, p_a);
-    }
-    for (; i < c.n_rounds; ++i) {
-        if (i & 1)
-            pipeline_step<D, NB, 1, true>(smem, lds0, c, i, w, s_b, s_a, p_a, p_b);
-        else
-            pipeline_step<D, NB, 0, true>(smem, lds0, c, i, w, s_a, s_b, p_b, p_a);
-    }
-    {
-        // PV product of the last round: its V operands still have to be fetched
-        const int last = c.n_rounds - 1;     // (w.tile_off already is the stage of tile last/2)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) w.v_addr[mb] = lds0 + w.tile_off + c.v_lane[mb];
-#pragma unroll
-        for (int j = 0; j < KS; ++j) {
-            const bf16x8 a = (last & 1) ? load_v_operand<D, NB, 1>(w.v_addr, j) : load_v_operand<D, NB, 0>(w.v_addr, j);
+        // ---- the pipeline, two steps at a time; step i_end only flushes the PV product of
+        // the last round (and a step past it, if the count is odd, adds nothing)
+        for (int i = i_begin; i <= i_end; i += 2) {
+            pipeline_step<D, NB, 0>(smem, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+        }
+
+        // ---- results.  A lane holds, for query `col` of block nb, rows
+        // d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T.
+        const bool whole = (t_begin == 0) && (uint32_t(t_stop) == tpu);
+        if (whole) {
+            __bf16 *oh = a.o + head_off;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const bf16x8 pj = (last & 1) ? p_b[nb][j / MB] : p_a[nb][j / MB];
-                w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pj, w.acc[j % MB][nb], 0, 0, 0);
+                const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
+                const float inv = 1.0f / l_tot;
+                const int qi = q0 + nb * 32 + col;
+                if (qi < n) {
+                    __bf16 *orow = oh + int64_t(qi) * stride_tok;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            union { uint2 u; bf16x2 p[2]; } ow;
+                            ow.p[0] = to_bf16x2(w.acc[mb][nb][4 * g + 0] * inv, w.acc[mb][nb][4 * g + 1] * inv);
+                            ow.p[1] = to_bf16x2(w.acc[mb][nb][4 * g + 2] * inv, w.acc[mb][nb][4 * g + 3] * inv);
+                            *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + half * 4) = ow.u;
+                        }
+                }
+            }
+        } else {
+            // partial: running maximum, row sum and unnormalised rows into this workgroup's slot
+            float *slot = a.ws + (size_t(2) * lp + (first_segment ? 0 : 1)) * slot_floats<D>();
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
+                const int row = wave * (32 * NB) + nb * 32 + col;
+                if (half == 0) {
+                    slot[row] = w.m_run[nb];
+                    slot[kBM + row] = l_tot;
+                }
+                float *arow = slot + 2 * kBM + row * D;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        *reinterpret_cast<float4 *>(arow + mb * 32 + g * 8 + half * 4) =
+                            make_float4(w.acc[mb][nb][4 * g + 0], w.acc[mb][nb][4 * g + 1],
+                                        w.acc[mb][nb][4 * g + 2], w.acc[mb][nb][4 * g + 3]);
             }
         }
-    }
-
-    // ---- normalise and store: lane holds, for query `col` of block nb, rows
-    // d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
-        const float inv = 1.0f / l_tot;
-        const int qi = q0 + nb * 32 + col;
-        if (qi < n) {
-            __bf16 *orow = oh + int64_t(qi) * stride_tok;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    union { uint2 u; bf16x2 p[2]; } ow;
-                    ow.p[0] = to_bf16x2(w.acc[mb][nb][4 * g + 0] * inv, w.acc[mb][nb][4 * g + 1] * inv);
-                    ow.p[1] = to_bf16x2(w.acc[mb][nb][4 * g + 2] * inv, w.acc[mb][nb][4 * g + 3] * inv);
-                    *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + half * 4) = ow.u;
-                }
-        }
+        it += uint32_t(t_stop - t_begin);
+        first_segment = false;
     }
 }
 
+// Merges the partial results of every unit that more than one workgroup worked on:
+//   m = max_s m_s,  l = sum_s l_s 2^(m_s - m),  O = sum_s O_s 2^(m_s - m) / l.
+// grid = (units, kBM / 32): a workgroup takes 32 query rows of one unit, a thread one row
+// and 16 consecutive d.
+template <int D>
+__global__ __launch_bounds__(32 * (D / 16)) void combine_kernel(const AttnParams a, uint32_t n_wg) {
+    constexpr int kChunks = D / 16;
+    const uint32_t unit = blockIdx.x;
+    const uint32_t W = a.total_work, tpu = uint32_t(a.tiles_per_unit);
+    const uint32_t lo = unit * tpu, hi = lo + tpu;            // the unit's iterations
+    // workgroup holding iteration x: the largest p with range_start(p) <= x
+    const uint32_t pf = uint32_t((uint64_t(lo + 1) * n_wg - 1) / W);
+    const uint32_t pl = uint32_t((uint64_t(hi) * n_wg - 1) / W);
+    if (pf == pl) return;                                      // computed whole by one workgroup
+    const int head = int(unit) / a.n_qtiles, qtile = int(unit) % a.n_qtiles;
+    const int row = int(blockIdx.y) * 32 + int(threadIdx.x) / kChunks, ch = int(threadIdx.x) % kChunks;
+    const int qi = qtile * kBM + row;
+    if (qi >= a.n) return;
+    // a workgroup's first segment lies in slot 0, a later (its last) one in slot 1
+    const float *slot0 = a.ws + (size_t(2) * pf + (range_start(pf, W, n_wg) >= lo ? 0 : 1)) * slot_floats<D>();
+    const size_t slot_step = size_t(2) * slot_floats<D>();    // every later workgroup starts inside the unit: slot 0
+    const float *first_later = a.ws + size_t(2) * (pf + 1) * slot_floats<D>();
+    float m = slot0[row];
+    for (uint32_t p = pf + 1; p <= pl; ++p) m = fmaxf(m, first_later[(p - pf - 1) * slot_step + row]);
+    float l = 0.0f, acc[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.0f;
+    for (uint32_t p = pf; p <= pl; ++p) {
+        const float *slot = p == pf ? slot0 : first_later + (p - pf - 1) * slot_step;
+        const float f = __builtin_amdgcn_exp2f(slot[row] - m);
+        l += slot[kBM + row] * f;
+        const float4 *src = reinterpret_cast<const float4 *>(slot + 2 * kBM + row * D + ch * 16);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float4 x = src[e];
+            acc[4 * e + 0] += x.x * f;
+            acc[4 * e + 1] += x.y * f;
+            acc[4 * e + 2] += x.z * f;
+            acc[4 * e + 3] += x.w * f;
+        }
+    }
+    const float inv = 1.0f / l;
+    union { uint4 u[2]; bf16x2 p[8]; } ow;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ow.p[e] = to_bf16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
+    uint4 *dst = reinterpret_cast<uint4 *>(a.o + int64_t(head) * a.stride_head + int64_t(qi) * a.stride_tok + ch * 16);
+    dst[0] = ow.u[0];
+    dst[1] = ow.u[1];
+}
+
+// Compute units of the current device (queried once per device).
+int device_compute_units() {
+    static int cached_dev = -1, cached_cus = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev != cached_dev) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached_cus = cus;
+        cached_dev = dev;
+    }
+    return cached_cus;
+}
+
+template <int D>
+int64_t workspace_bytes_for(int cus) { return int64_t(2) * cus * slot_floats<D>() * int64_t(sizeof(float)); }
+
 template <int D, int NB>
-int launch(const void *q, const void *k, const void *v, void *o, int n, int heads, int64_t stride_tok,
-           int64_t stride_head, float scale, hipStream_t stream) {
+int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hipStream_t stream) {
     static bool attr_set = false;   // per process; the attribute is per function
-    auto kern = attention_kernel<D, NB>;
+    const void *kern = reinterpret_cast<const void *>(&attention_kernel<D, NB>);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Tile<D, NB>::kBytes);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, Tile<D, NB>::kBytes);
         if (e != hipSuccess) {
             lp::set_last_hip_error(int(e));
             return LP_ERR_HIP;
         }
         attr_set = true;
     }
-    const int n_qtiles = (n + kBM - 1) / kBM;
-    const dim3 grid(uint32_t(n_qtiles) * uint32_t(heads));
-    const float scale_log2e = scale * 1.4426950408889634f;
-    return lp::launch_kernel(reinterpret_cast<const void *>(kern), grid, dim3(waves_of(NB) * 64), Tile<D, NB>::kBytes, stream,
-                             static_cast<const __bf16 *>(q), static_cast<const __bf16 *>(k),
-                             static_cast<const __bf16 *>(v), static_cast<__bf16 *>(o), n, heads, stride_tok,
-                             stride_head, scale_log2e, n_qtiles);
+    a.n_qtiles = (a.n + kBM - 1) / kBM;
+    a.tiles_per_unit = (a.n + kBN - 1) / kBN;
+    a.n_units = a.n_qtiles * heads;
+    a.total_work = uint32_t(a.n_units) * uint32_t(a.tiles_per_unit);
+    a.ws = nullptr;
+    uint32_t n_wg = uint32_t(a.n_units);          // one workgroup per unit: nothing is partial
+    const int cus = device_compute_units();
+    if (workspace != nullptr && cus > 0 && workspace_bytes >= workspace_bytes_for<D>(cus)) {
+        // Candidate: one workgroup per compute unit (fewer when that would leave them less
+        // than kMinTiles tiles each), every one with an equal share of the (unit, tile)
+        // space.  Costs in units of one tile's time: a workgroup that starts or ends inside
+        // a unit pays a second prologue and a partial store, and the merge kernel follows.
+        constexpr uint32_t kMinTiles = 8, kSplitCost = 6, kMergeCost = 3;
+        uint32_t p = a.total_work / kMinTiles;
+        if (p > uint32_t(cus)) p = uint32_t(cus);
+        if (p > uint32_t(a.n_units) || (p == uint32_t(cus) && a.n_units % cus != 0)) {
+            const uint32_t waves_of_units = (uint32_t(a.n_units) + cus - 1) / cus;
+            const uint32_t t_plain = waves_of_units * uint32_t(a.tiles_per_unit);
+            const uint32_t t_split = (a.total_work + p - 1) / p + kSplitCost + kMergeCost;
+            if (t_split < t_plain) {
+                n_wg = p;
+                a.ws = static_cast<float *>(workspace);
+            }
+        }
+    }
+    int rc = lp::launch_kernel(kern, dim3(n_wg), dim3(waves_of(NB) * 64), Tile<D, NB>::kBytes, stream, a);
+    if (rc != LP_OK || a.ws == nullptr) return rc;
+    return lp::launch_kernel(reinterpret_cast<const void *>(&combine_kernel<D>), dim3(uint32_t(a.n_units), kBM / 32),
+                             dim3(32 * (D / 16)), 0, stream, a, n_wg);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
 
+extern "C" int64_t lp_attention_workspace_size(int32_t head_dim) {
+    if (head_dim != 64 && head_dim != 128) return LP_ERR_UNSUPPORTED;
+    const int cus = device_compute_units();
+    if (cus <= 0) return LP_ERR_HIP;
+    return head_dim == 128 ? workspace_bytes_for<128>(cus) : workspace_bytes_for<64>(cus);
+}
+
 extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
                             int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
-                            float scale, void *stream) {
+                            float scale, void *workspace, int64_t workspace_bytes, void *stream) {
     if (n_tokens < 0 || heads < 1) return LP_ERR_INVALID_ARG;
     if (head_dim != 64 && head_dim != 128) return LP_ERR_UNSUPPORTED;
     if (n_tokens == 0) return LP_OK;
     if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return LP_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return LP_ERR_INVALID_ARG;
+    if (workspace != nullptr && (!aligned16(workspace) || workspace_bytes < 0)) return LP_ERR_INVALID_ARG;
     if (stride_head < head_dim || stride_head % 8 != 0 || stride_tok % 8 != 0) return LP_ERR_INVALID_ARG;
     // rows of different (token, head) pairs must not overlap: either token-major or head-major
     const bool token_major = stride_tok >= int64_t(heads) * stride_head;
     const bool head_major = stride_head >= n_tokens * stride_tok && stride_tok >= head_dim;
     if (!token_major && !head_major) return LP_ERR_INVALID_ARG;
-    if (n_tokens > (int64_t(1) << 24) || int64_t(heads) * ((n_tokens + kBM - 1) / kBM) > (int64_t(1) << 30))
-        return LP_ERR_UNSUPPORTED;
+    // 32-bit addressing inside one head: byte offsets below 2^31, work items below 2^31
+    if (n_tokens > (int64_t(1) << 24) || (n_tokens * stride_tok + head_dim) * 2 >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
+    const int64_t units = int64_t(heads) * ((n_tokens + kBM - 1) / kBM);
+    if (units * ((n_tokens + kBN - 1) / kBN) >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
     if (!(scale > 0.0f)) scale = 1.0f / sqrtf(float(head_dim));
+    AttnParams a{};
+    a.q = static_cast<const __bf16 *>(q);
+    a.k = static_cast<const __bf16 *>(k);
+    a.v = static_cast<const __bf16 *>(v);
+    a.o = static_cast<__bf16 *>(o);
+    a.stride_tok = stride_tok;
+    a.stride_head = stride_head;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.n = int(n_tokens);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (head_dim == 128)
-        return launch<128, kBlocksPerWave>(q, k, v, o, int(n_tokens), heads, stride_tok, stride_head, scale, st);
-    return launch<64, kBlocksPerWave>(q, k, v, o, int(n_tokens), heads, stride_tok, stride_head, scale, st);
+    if (head_dim == 128) return launch<128, kBlocksPerWave>(a, heads, workspace, workspace_bytes, st);
+    return launch<64, kBlocksPerWave>(a, heads, workspace, workspace_bytes, st);
 }

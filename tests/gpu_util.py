@@ -44,12 +44,27 @@ def from_dev_bf16(t: torch.Tensor) -> np.ndarray:
     return synth.bf16_bits_to_f32(bits)
 
 
-def hip_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float = 0.0) -> np.ndarray:
-    """q, k, v: uint16 [n, heads, d] token-major.  Returns float32 [n, heads, d]."""
+_workspaces = {}
+
+
+def workspace(head_dim: int):
+    """(tensor, bytes): device scratch for lp_attention, allocated once per head_dim and
+    filled with NaN so that any read of a slot nobody wrote shows up in the result."""
+    if head_dim not in _workspaces:
+        nbytes = lp.lp_attention_workspace_size(head_dim)
+        _workspaces[head_dim] = (torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda"), nbytes)
+    return _workspaces[head_dim]
+
+
+def hip_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float = 0.0, balanced: bool = True) -> np.ndarray:
+    """q, k, v: uint16 [n, heads, d] token-major.  Returns float32 [n, heads, d].
+    balanced=True passes a workspace (the launch configuration the benchmark times);
+    False launches one workgroup per query tile and head."""
     n, heads, d = q.shape
     qd, kd, vd = to_dev_bf16(q), to_dev_bf16(k), to_dev_bf16(v)
     od = torch.full((n, heads, d), float("nan"), dtype=torch.bfloat16, device="cuda")
-    lp.lp_attention(qd, kd, vd, od, n, heads, d, heads * d, d, scale, stream())
+    ws, ws_bytes = workspace(d) if balanced else (None, 0)
+    lp.lp_attention(qd, kd, vd, od, n, heads, d, heads * d, d, scale, ws, ws_bytes, stream())
     torch.cuda.synchronize()
     return from_dev_bf16(od)
 

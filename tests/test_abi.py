@@ -116,8 +116,11 @@ def test_device_calls_reject_bad_arguments_without_a_gpu():
     plan = lp.lp_plan_create((16, 5, 16, 16), (1, 2, 2), 2, 2, overlap_patches=1)
     assert lib.lp_partition(plan.handle, None, None, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_reconstruct(None, 16, 16, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 96, 384, 96, 0.0, None) == lp.LP_ERR_UNSUPPORTED
-    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 60, 0.0, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention(16, 16, 16, 8, 10, 4, 64, 256, 64, 0.0, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention(None, None, None, None, 0, 4, 64, 256, 64, 0.0, None) == lp.LP_OK
-    assert lib.lp_attention(None, None, None, None, -1, 4, 64, 256, 64, 0.0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 96, 384, 96, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED
+    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 60, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention(16, 16, 16, 8, 10, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention(None, None, None, None, 0, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_OK
+    assert lib.lp_attention(None, None, None, None, -1, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 64, 0.0, 8, 1 << 20, None) == lp.LP_ERR_INVALID_ARG   # workspace alignment
+    assert lib.lp_attention(16, 16, 16, 16, 1 << 22, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED  # offsets past 2^31
+    assert lib.lp_attention_workspace_size(96) == lp.LP_ERR_UNSUPPORTED

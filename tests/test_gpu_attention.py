@@ -12,15 +12,33 @@ from paper_2512_07350_amd import synth
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("balanced", [True, False], ids=["balanced", "tile-per-workgroup"])
 @pytest.mark.parametrize("hd", [64, 128])
-@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 63, 64, 65, 200, 255, 256, 257, 320, 513, 1000])
-def test_small_full_oracle(n, hd):
+@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 200, 255, 256, 257, 320, 513, 1000])
+def test_small_full_oracle(n, hd, balanced):
     from tests import gpu_util as g
     heads = 3
     q, k, v = synth.qkv_bf16(4000 + 2 * n + hd, n, heads, hd)
-    got = g.hip_attention(q, k, v)
+    got = g.hip_attention(q, k, v, balanced=balanced)
     want = orc.attention(q, k, v)
     g.assert_attention_close(got, want, "n=%d hd=%d" % (n, hd))
+
+
+@pytest.mark.parametrize("n,heads,hd", [(3000, 1, 128), (2048, 2, 128), (700, 5, 64), (5000, 7, 64), (64, 40, 128)])
+def test_work_split_across_workgroups(n, heads, hd):
+    """Few (query tile, head) units: with a workspace every unit is shared by several
+    workgroups and the merge kernel produces the output; must agree with the oracle and
+    with the unsplit launch."""
+    from tests import gpu_util as g
+    q, k, v = synth.qkv_bf16(9000 + n + heads, n, heads, hd)
+    rows = synth.sample_rows(n, 160, seed=n, tile=256)
+    want = orc.attention(q, k, v, rows=rows)
+    split = g.hip_attention(q, k, v, balanced=True)
+    plain = g.hip_attention(q, k, v, balanced=False)
+    g.assert_attention_close(split[rows], want, "split n=%d" % n)
+    g.assert_attention_close(plain[rows], want, "plain n=%d" % n)
+    assert np.all(np.isfinite(split)) and np.all(np.isfinite(plain))
+    assert np.max(np.abs(split - plain)) <= 2e-2
 
 
 def test_tiny_config_partitions_full_oracle():
@@ -31,11 +49,12 @@ def test_tiny_config_partitions_full_oracle():
         g.assert_attention_close(g.hip_attention(q, k, v), orc.attention(q, k, v), "tiny k=%d" % k_part)
 
 
-def test_medium_full_oracle_spans_many_tiles():
+@pytest.mark.parametrize("balanced", [True, False], ids=["balanced", "tile-per-workgroup"])
+def test_medium_full_oracle_spans_many_tiles(balanced):
     # 3276 tokens (the smallest 33-frame partition along H), all rows, 2 heads
     from tests import gpu_util as g
     q, k, v = synth.qkv_bf16(77, 3276, 2, 128)
-    g.assert_attention_close(g.hip_attention(q, k, v), orc.attention(q, k, v), "n=3276")
+    g.assert_attention_close(g.hip_attention(q, k, v, balanced=balanced), orc.attention(q, k, v), "n=3276")
 
 
 def test_explicit_scale_and_default_scale():
@@ -84,10 +103,14 @@ def test_head_major_strides_and_in_place_views():
     want = g.hip_attention(q, k, v)
     qd, kd, vd = (g.to_dev_bf16(np.ascontiguousarray(a.transpose(1, 0, 2))) for a in (q, k, v))
     od = torch.zeros((heads, n, hd), dtype=torch.bfloat16, device="cuda")
-    lp.lp_attention(qd, kd, vd, od, n, heads, hd, hd, n * hd, 0.0, g.stream())
+    lp.lp_attention(qd, kd, vd, od, n, heads, hd, hd, n * hd, 0.0, None, 0, g.stream())
     torch.cuda.synchronize()
     got = g.from_dev_bf16(od).transpose(1, 0, 2)
-    assert np.array_equal(got, want)
+    assert np.array_equal(got, g.hip_attention(q, k, v, balanced=False))
+    ws, ws_bytes = g.workspace(hd)
+    lp.lp_attention(qd, kd, vd, od, n, heads, hd, hd, n * hd, 0.0, ws, ws_bytes, g.stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(g.from_dev_bf16(od).transpose(1, 0, 2), want)
 
 
 def test_zero_tokens_is_a_noop():
