@@ -265,10 +265,12 @@ __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
 // Even steps open tile t+1 (t = i/2): they wait for its loads, pass the barrier (after which
 // every wave has fetched its last operand from tile t-2), and refill that stage with tile
 // t+kStages-2.
-// The same code runs at the ends of a segment: rounds that do not exist get scores -inf
-// (probabilities 0) and the round before the first has probabilities 0, so the products
-// issued for them add nothing; their operands are read from valid, if stale, LDS addresses.
-template <int D, int NB, int SUB>
+// The same code runs at the ends of a segment: with MASK, keys past the segment's end get
+// scores -inf (probabilities 0), and the round before the first has probabilities 0, so
+// the products issued for rounds that do not exist add nothing; their operands are read
+// from valid, if stale, LDS addresses.  MASK = false is for steps whose rounds i+1 lie
+// wholly inside the segment and keeps the step free of conditionals.
+template <int D, int NB, int SUB, bool MASK>
 __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D, NB> &c, int i, bool first,
                                               Pipe<D, NB> &w, f32x16 (&s_cur)[NB], f32x16 (&s_nxt)[NB],
                                               bf16x8 (&p_prev)[NB][2], bf16x8 (&p_cur)[NB][2]) {
@@ -316,7 +318,7 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D,
             w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], p_prev[nb][j / MB], w.acc[j % MB][nb], 0, 0, 0);
         w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
     }
-    if ((i + 2) * 32 > c.key_end) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
+    if (MASK) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
     raise_maximum<D, NB>(s_nxt, p_cur, w.acc, w.m_run, w.l_run);
 }
 
@@ -507,9 +509,14 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 
         // ---- the pipeline, two steps at a time; step i_end only flushes the PV product of
         // the last round (and a step past it, if the count is odd, adds nothing)
-        for (int i = i_begin; i <= i_end; i += 2) {
-            pipeline_step<D, NB, 0>(smem, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
-            pipeline_step<D, NB, 1>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+        int i = i_begin;
+        for (; (i + 3) * 32 <= c.key_end; i += 2) {      // rounds i+1 and i+2 are whole
+            pipeline_step<D, NB, 0, false>(smem, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1, false>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+        }
+        for (; i <= i_end; i += 2) {
+            pipeline_step<D, NB, 0, true>(smem, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1, true>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
         }
 
         // ---- results.  A lane holds, for query `col` of block nb, rows
