@@ -71,20 +71,27 @@ __global__ __launch_bounds__(kThreads) void partition_kernel(const float *__rest
     const FastDiv run = a.run[k];
     const V *src = reinterpret_cast<const V *>(z) + a.src_off[k];
     V *dst = reinterpret_cast<V *>(subs) + a.dst_off[k];
-    V val[UNROLL];
+    if (blockIdx.x * (kThreads * UNROLL) + kThreads * UNROLL <= n_vec) {
+        // whole block in range: all loads in flight before the first store
+        V val[UNROLL];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const uint32_t i = base + u * kThreads;
-        if (i < n_vec) {
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t i = base + u * kThreads;
             const uint32_t o = fastdiv(i, run);
             const uint32_t r = i - o * run.d;
             val[u] = src[uint64_t(o) * a.src_stride + r];
         }
-    }
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) {
-        const uint32_t i = base + u * kThreads;
-        if (i < n_vec) dst[i] = val[u];
+        for (int u = 0; u < UNROLL; ++u) dst[base + u * kThreads] = val[u];
+    } else {
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t i = base + u * kThreads;
+            if (i < n_vec) {
+                const uint32_t o = fastdiv(i, run);
+                const uint32_t r = i - o * run.d;
+                dst[i] = src[uint64_t(o) * a.src_stride + r];
+            }
+        }
     }
 }
 
