@@ -38,7 +38,11 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=1, help="index into the benchmark configurations (default 1)")
     ap.add_argument("--layers", type=int, default=0, help="attention calls per partition per step (0 = the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--traffic-json", default="", help="file with measured HBM bytes per attention launch (optional)")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "attention_traffic.json"),
+                    help="measured HBM bytes per attention launch (written from rocprofv3 --pmc runs; see profiles/)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain device copy of 256 MiB (known size) so that a rocprofv3 --pmc run "
+                         "of this command holds the reference dispatch the byte counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; run it with --gpus 1 (got %d). "
@@ -140,12 +144,21 @@ def main() -> int:
             att_launches += 1
             d["ms"] += t; d["flops"] += flops_of(n); d["launches"] += 1
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                       # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+
     ms_per_step = wall * 1e3 / args.steps
     value = att_flops / wall / 1e12
     achieved = att_flops / (att_ms * 1e-3) / 1e12
     traffic = None
     if args.traffic_json and os.path.exists(args.traffic_json):
-        traffic = json.load(open(args.traffic_json)).get("attention_bytes_per_launch")
+        rec = json.load(open(args.traffic_json))
+        if rec.get("workload") == w.name:
+            traffic = rec.get("attention_bytes_per_launch")
 
     result = {
         "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s",
