@@ -322,19 +322,26 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D,
     raise_maximum<D, NB>(s_nxt, p_cur, w.acc, w.m_run, w.l_run);
 }
 
-// Launch parameters.  The iteration space is (unit, key tile): a unit is one 256-row query
-// tile of one head, and every unit walks tiles_per_unit tiles of 64 keys.  The grid's
-// workgroups cut that space into equal contiguous ranges, so a workgroup may start and end
-// in the middle of a unit; such partial results go to `ws` and are merged by
-// combine_kernel.  With one workgroup per unit nothing is partial.
+// Launch parameters.  A unit is one 256-row query tile of one head; every unit walks
+// tiles_per_unit tiles of 64 keys.  With P workgroups, the units are served in two parts:
+//  * the first shared_units units form a (unit, key tile) iteration space of
+//    shared_work = shared_units * tiles_per_unit tiles that is cut into shared_wgs <= P equal
+//    contiguous ranges (never empty), so a workgroup may start and end in the middle of a
+//    unit; such partial results go to `ws` and are merged by combine_kernel;
+//  * the remaining whole_rounds * P units are taken whole, unit shared_units + r*P + p by
+//    workgroup p in round r: the workgroups of an XCD then walk the keys of one head in
+//    step and share its K/V stream through the L2.
+// One workgroup per unit (nothing shared) is shared_units = 0, whole_rounds = 1.
 struct AttnParams {
     const __bf16 *q, *k, *v;
     __bf16 *o;
     float *ws;                 // slots for partial results: 2 per workgroup
     int64_t stride_tok, stride_head;
     float scale_log2e;
-    int n, n_qtiles, tiles_per_unit, n_units;
-    uint32_t total_work;       // n_units * tiles_per_unit
+    int n, n_qtiles, tiles_per_unit;
+    int shared_units, whole_rounds;
+    uint32_t shared_work;      // shared_units * tiles_per_unit
+    uint32_t shared_wgs;       // workgroups 0 .. shared_wgs-1 (logical order) take part in the shared space
 };
 
 // A slot holds, for the 256 query rows of a unit: m[256], l[256], then the unnormalised
@@ -387,17 +394,31 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         c.v_voff[i] = uint32_t(row * stride_tok * 2) + 16 * (gran ^ T::swz_v(row));
     }
 
-    // ---- this workgroup's range of the (unit, tile) iteration space
+    // ---- this workgroup's range of the shared (unit, tile) space, then its whole units
     const uint32_t lp = logical_workgroup(blockIdx.x, gridDim.x);
-    uint32_t it = range_start(lp, a.total_work, gridDim.x);
-    const uint32_t it_end = range_start(lp + 1, a.total_work, gridDim.x);
+    const bool sharing = lp < a.shared_wgs;
+    uint32_t it = sharing ? range_start(lp, a.shared_work, a.shared_wgs) : 0u;
+    const uint32_t it_end = sharing ? range_start(lp + 1, a.shared_work, a.shared_wgs) : 0u;
     const uint32_t tpu = uint32_t(a.tiles_per_unit);
+    int whole_round = 0;
     bool first_segment = true;
 
-    while (it < it_end) {
-        const uint32_t unit = it / tpu;
-        const int t_begin = int(it - unit * tpu);
-        const int t_stop = int(min(tpu, uint32_t(t_begin) + (it_end - it)));
+    while (true) {
+        uint32_t unit;
+        int t_begin, t_stop;
+        if (it < it_end) {
+            unit = it / tpu;
+            t_begin = int(it - unit * tpu);
+            t_stop = int(min(tpu, uint32_t(t_begin) + (it_end - it)));
+            it += uint32_t(t_stop - t_begin);
+        } else if (whole_round < a.whole_rounds) {
+            unit = uint32_t(a.shared_units) + uint32_t(whole_round) * gridDim.x + lp;
+            t_begin = 0;
+            t_stop = int(tpu);
+            ++whole_round;
+        } else {
+            break;
+        }
         const int head = int(unit) / a.n_qtiles;
         const int qtile = int(unit) % a.n_qtiles;
         const int64_t head_off = int64_t(head) * a.stride_head;
@@ -563,7 +584,6 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                                         w.acc[mb][nb][4 * g + 2], w.acc[mb][nb][4 * g + 3]);
             }
         }
-        it += uint32_t(t_stop - t_begin);
         first_segment = false;
     }
 }
@@ -576,8 +596,8 @@ template <int D>
 __global__ __launch_bounds__(32 * (D / 16)) void combine_kernel(const AttnParams a, uint32_t n_wg) {
     constexpr int kChunks = D / 16;
     const uint32_t unit = blockIdx.x;
-    const uint32_t W = a.total_work, tpu = uint32_t(a.tiles_per_unit);
-    const uint32_t lo = unit * tpu, hi = lo + tpu;            // the unit's iterations
+    const uint32_t W = a.shared_work, tpu = uint32_t(a.tiles_per_unit);
+    const uint32_t lo = unit * tpu, hi = lo + tpu;            // the unit's iterations in the shared space
     // workgroup holding iteration x: the largest p with range_start(p) <= x
     const uint32_t pf = uint32_t((uint64_t(lo + 1) * n_wg - 1) / W);
     const uint32_t pl = uint32_t((uint64_t(hi) * n_wg - 1) / W);
@@ -649,33 +669,48 @@ int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hi
     }
     a.n_qtiles = (a.n + kBM - 1) / kBM;
     a.tiles_per_unit = (a.n + kBN - 1) / kBN;
-    a.n_units = a.n_qtiles * heads;
-    a.total_work = uint32_t(a.n_units) * uint32_t(a.tiles_per_unit);
+    const uint32_t units = uint32_t(a.n_qtiles) * uint32_t(heads), tpu = uint32_t(a.tiles_per_unit);
+    // default: one workgroup per unit, nothing shared
+    uint32_t n_wg = units;
     a.ws = nullptr;
-    uint32_t n_wg = uint32_t(a.n_units);          // one workgroup per unit: nothing is partial
+    a.shared_units = 0;
+    a.whole_rounds = 1;
+    a.shared_work = 0;
+    a.shared_wgs = 0;
     const int cus = device_compute_units();
     if (workspace != nullptr && cus > 0 && workspace_bytes >= workspace_bytes_for<D>(cus)) {
-        // Candidate: one workgroup per compute unit (fewer when that would leave them less
-        // than kMinTiles tiles each), every one with an equal share of the (unit, tile)
-        // space.  Costs in units of one tile's time: a workgroup that starts or ends inside
-        // a unit pays a second prologue and a partial store, and the merge kernel follows.
+        // Candidate: one workgroup per compute unit takes floor(units / #CU) rounds of whole
+        // units, and the units left over are shared evenly by as many workgroups as get at least
+        // kMinTiles tiles each.  Costs in units of one tile's time: a workgroup that starts or
+        // ends inside a unit pays a second prologue and a partial store, and the merge kernel
+        // follows.
         constexpr uint32_t kMinTiles = 8, kSplitCost = 6, kMergeCost = 3;
-        uint32_t p = a.total_work / kMinTiles;
-        if (p > uint32_t(cus)) p = uint32_t(cus);
-        if (p > uint32_t(a.n_units) || (p == uint32_t(cus) && a.n_units % cus != 0)) {
-            const uint32_t waves_of_units = (uint32_t(a.n_units) + cus - 1) / cus;
-            const uint32_t t_plain = waves_of_units * uint32_t(a.tiles_per_unit);
-            const uint32_t t_split = (a.total_work + p - 1) / p + kSplitCost + kMergeCost;
-            if (t_split < t_plain) {
-                n_wg = p;
-                a.ws = static_cast<float *>(workspace);
+        const uint32_t p = units < uint32_t(cus) ? units : uint32_t(cus);     // workgroups
+        const uint32_t rounds = units >= uint32_t(cus) ? units / p : 0;       // whole-unit rounds
+        const uint32_t shared = units - rounds * p;
+        if (shared > 0) {
+            uint32_t sharers = shared * tpu / kMinTiles;                      // never more than tiles
+            if (sharers > uint32_t(cus)) sharers = uint32_t(cus);
+            if (sharers > shared || rounds > 0) {                             // else sharing adds no parallelism
+                if (sharers < 1) sharers = 1;
+                const uint32_t wgs = rounds > 0 ? p : sharers;
+                const uint32_t t_plain = ((units + cus - 1) / cus) * tpu;
+                const uint32_t t_split = rounds * tpu + (shared * tpu + sharers - 1) / sharers + kSplitCost + kMergeCost;
+                if (t_split < t_plain) {
+                    n_wg = wgs;
+                    a.ws = static_cast<float *>(workspace);
+                    a.shared_units = int(shared);
+                    a.whole_rounds = int(rounds);
+                    a.shared_work = shared * tpu;
+                    a.shared_wgs = sharers;
+                }
             }
         }
     }
     int rc = lp::launch_kernel(kern, dim3(n_wg), dim3(waves_of(NB) * 64), Tile<D, NB>::kBytes, stream, a);
     if (rc != LP_OK || a.ws == nullptr) return rc;
-    return lp::launch_kernel(reinterpret_cast<const void *>(&combine_kernel<D>), dim3(uint32_t(a.n_units), kBM / 32),
-                             dim3(32 * (D / 16)), 0, stream, a, n_wg);
+    return lp::launch_kernel(reinterpret_cast<const void *>(&combine_kernel<D>), dim3(uint32_t(a.shared_units), kBM / 32),
+                             dim3(32 * (D / 16)), 0, stream, a, a.shared_wgs);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
