@@ -151,20 +151,19 @@ __device__ __forceinline__ void mask_scores(int r, int half, int n, f32x16 (&s)[
     }
 }
 
-// bf16 probabilities exp2(s - m) laid out as PV operands; the row sum adds the rounded values.
+// bf16 probabilities exp2(s) laid out as PV operands (the scores are already relative to the
+// running maximum); the row sum adds the rounded values.
 template <int NB>
-__device__ __forceinline__ void probabilities(const f32x16 (&s)[NB], bf16x8 (&p)[NB][2], const float (&m_run)[NB],
-                                              float (&l_run)[NB]) {
+__device__ __forceinline__ void probabilities(const f32x16 (&s)[NB], bf16x8 (&p)[NB][2], float (&l_run)[NB]) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         Pack16 lo, hi;
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-        const float m = m_run[nb];
         float l = l_run[nb];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            lo.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][2 * e] - m), __builtin_amdgcn_exp2f(s[nb][2 * e + 1] - m));
-            hi.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][8 + 2 * e] - m), __builtin_amdgcn_exp2f(s[nb][8 + 2 * e + 1] - m));
+            lo.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][2 * e]), __builtin_amdgcn_exp2f(s[nb][2 * e + 1]));
+            hi.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][8 + 2 * e]), __builtin_amdgcn_exp2f(s[nb][8 + 2 * e + 1]));
             l = __builtin_amdgcn_fdot2_f32_bf16(lo.p[e], ones, l, false);
             l = __builtin_amdgcn_fdot2_f32_bf16(hi.p[e], ones, l, false);
         }
@@ -174,25 +173,30 @@ __device__ __forceinline__ void probabilities(const f32x16 (&s)[NB], bf16x8 (&p)
     }
 }
 
-// Lazy running maximum.  s holds scores that will be exponentiated NEXT; if any of them
-// is more than kRescaleThreshold above the running maximum, raise the maximum and rescale
-// what was accumulated under the old one: the output accumulators, the row sums, and the
+// Lazy running maximum.  Score accumulators start at neg_m = -m (m = running maximum, log2
+// units), so s holds scores relative to m that will be exponentiated NEXT.  If any of them
+// exceeds kRescaleThreshold, raise the maximum by delta and rescale what was accumulated
+// under the old one: these scores, the output accumulators, the row sums, and the
 // probabilities p_pending that have been computed but not yet multiplied into acc.
 template <int D, int NB>
-__device__ __forceinline__ void raise_maximum(const f32x16 (&s)[NB], bf16x8 (&p_pending)[NB][2],
-                                              f32x16 (&acc)[D / 32][NB], float (&m_run)[NB], float (&l_run)[NB]) {
+__device__ __forceinline__ void raise_maximum(f32x16 (&s)[NB], f32x16 (&neg_m)[NB], bf16x8 (&p_pending)[NB][2],
+                                              f32x16 (&acc)[D / 32][NB], float (&l_run)[NB]) {
     bool raise = false;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) raise = raise || (max16(s[nb]) - m_run[nb] > kRescaleThreshold);
+    for (int nb = 0; nb < NB; ++nb) raise = raise || (max16(s[nb]) > kRescaleThreshold);
     if (__any(raise)) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             float tmax = max16(s[nb]);
             tmax = fmaxf(tmax, other_half(tmax));
-            const float m_new = fmaxf(m_run[nb], tmax);      // the maximum never goes down
-            const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-            m_run[nb] = m_new;
+            const float delta = fmaxf(tmax, 0.0f);           // the maximum never goes down
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
             l_run[nb] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                s[nb][i] -= delta;
+                neg_m[nb][i] -= delta;
+            }
 #pragma unroll
             for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
@@ -239,7 +243,8 @@ struct Pipe {
     bf16x8 qreg[NB][D / 16];       // Q^T operands (pre-scaled)
     bf16x8 opreg[D / 16];          // LDS operands: K rows before a score product, V^T blocks before a PV product
     f32x16 acc[D / 32][NB];        // O^T accumulators
-    float m_run[NB];               // running maximum (log2 units), common to both half-waves
+    f32x16 neg_m[NB];              // -m in every element (m = running maximum, log2 units, common to
+                                   // both half-waves): the initial value of every score accumulator
     float l_run[NB];               // this lane's share of the running sum
     uint32_t k_addr[D / 16];       // LDS addresses of the K operands in the stage at k_off
     uint32_t v_addr[D / 32];       // LDS addresses of the V operands in the stage at v_off
@@ -300,17 +305,14 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D,
         }
     }
 
-    f32x16 zero16;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) zero16[r] = 0.0f;
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-            s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], w.qreg[nb][j], j == 0 ? zero16 : s_nxt[nb], 0, 0, 0);
+            s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], w.qreg[nb][j], j == 0 ? w.neg_m[nb] : s_nxt[nb], 0, 0, 0);
         w.opreg[j] = load_v_operand<D, NB, 1 - SUB>(w.v_addr, j);
     }
-    probabilities<NB>(s_cur, p_cur, w.m_run, w.l_run);
+    probabilities<NB>(s_cur, p_cur, w.l_run);
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
 #pragma unroll
@@ -319,7 +321,7 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D,
         w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
     }
     if (MASK) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
-    raise_maximum<D, NB>(s_nxt, p_cur, w.acc, w.m_run, w.l_run);
+    raise_maximum<D, NB>(s_nxt, w.neg_m, p_cur, w.acc, w.l_run);
 }
 
 // Launch parameters.  A unit is one 256-row query tile of one head; every unit walks
@@ -519,8 +521,13 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         if ((i_begin + 1) * 32 > c.key_end) mask_scores<NB>(i_begin, half, c.key_end, s_a);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            const float tmax = max16(s_a[nb]);
-            w.m_run[nb] = fmaxf(tmax, other_half(tmax));
+            float tmax = max16(s_a[nb]);
+            tmax = fmaxf(tmax, other_half(tmax));
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                w.neg_m[nb][r] = -tmax;
+                s_a[nb][r] -= tmax;
+            }
             s_b[nb] = s_a[nb];
             Pack16 z;
             z.u = make_uint4(0, 0, 0, 0);
@@ -571,7 +578,7 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                 const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
                 const int row = wave * (32 * NB) + nb * 32 + col;
                 if (half == 0) {
-                    slot[row] = w.m_run[nb];
+                    slot[row] = -w.neg_m[nb][0];
                     slot[kBM + row] = l_tot;
                 }
                 float *arow = slot + 2 * kBM + row * D;
