@@ -107,6 +107,8 @@ struct ReconstructArgs {
     uint32_t inner_vec;                 // inner / VEC (X_PER_ELEM = false), else unused
     FastDiv lat_run;                    // extent * inner, in vectors
     FastDiv inner_div;                  // inner, in vectors (X_PER_ELEM = false)
+    FastDiv core_div;                   // L * p: core length in latent units (LANE_K)
+    int32_t ovl;                        // O * p: overlap in latent units (LANE_K)
 };
 
 // Eq. 12 at local position j; the cases in the order the paper gives them.
@@ -116,13 +118,57 @@ __device__ __forceinline__ float ramp_weight(int32_t j, int32_t len, int32_t ds,
     return __fdiv_rn(float(len - j), float(de));
 }
 
+// One partition's term of Eq. 15-16 for the vector at x0 (local position j0 in partition k).
+template <int VEC, bool X_PER_ELEM>
+__device__ __forceinline__ void blend_term(const typename VecT<VEC>::type p, int32_t j0, int32_t len, int32_t ds,
+                                           int32_t de, float (&A)[VEC], float (&Z)[VEC]) {
+    const float *pf = reinterpret_cast<const float *>(&p);
+    if (X_PER_ELEM) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            const float w = ramp_weight(j0 + c, len, ds, de);
+            A[c] = __fadd_rn(A[c], __fmul_rn(w, pf[c]));   // Eq. 15: rounded product, rounded sum
+            Z[c] = __fadd_rn(Z[c], w);                      // Eq. 16
+        }
+    } else {
+        const float w = ramp_weight(j0, len, ds, de);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            A[c] = __fadd_rn(A[c], __fmul_rn(w, pf[c]));
+            Z[c] = __fadd_rn(Z[c], w);
+        }
+    }
+}
+
 // Eq. 13-17.  X_PER_ELEM: the partition dim is the vectorised (fastest) one, so
 // each element of a vector has its own coordinate x and its own weight.
-template <int VEC, bool X_PER_ELEM>
+// LANE_K: the lanes of a wave sit at many different x (short inner runs), so a
+// wave as a whole touches every partition.  Each lane then walks only the k
+// range that can cover its x -- from s_k >= k L p - O p and e_k <= (k+1) L p + O p,
+// floor((x - O p) / (L p)) <= k <= floor((x + O p) / (L p)) -- with the plan
+// held in LDS; the test against s_k and e_k still decides.  Otherwise a wave
+// shares one or two x and the loop over all k with scalar loads is cheaper.
+// Both visit the covering partitions in ascending k, so the sums are identical.
+template <int VEC, bool X_PER_ELEM, bool LANE_K>
 __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__restrict__ preds,
                                                                float *__restrict__ out,
                                                                const ReconstructArgs a) {
     using V = typename VecT<VEC>::type;
+    __shared__ int32_t plan_s[LANE_K ? LP_MAX_PARTS : 1], plan_e[LANE_K ? LP_MAX_PARTS : 1],
+        plan_len[LANE_K ? LP_MAX_PARTS : 1], plan_ds[LANE_K ? LP_MAX_PARTS : 1], plan_de[LANE_K ? LP_MAX_PARTS : 1];
+    __shared__ uint32_t plan_off[LANE_K ? LP_MAX_PARTS : 1];
+    if (LANE_K) {
+        const int t = threadIdx.x;
+        if (t < a.K) {
+            plan_s[t] = a.s[t];
+            plan_e[t] = a.e[t];
+            plan_len[t] = a.len[t];
+            plan_ds[t] = a.delta_start[t];
+            plan_de[t] = a.delta_end[t];
+            plan_off[t] = a.off[t];
+        }
+        __syncthreads();
+    }
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= a.n_vec) return;
     const uint32_t o = fastdiv(i, a.lat_run);
@@ -141,32 +187,29 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__re
 #pragma unroll
     for (int c = 0; c < VEC; ++c) { A[c] = 0.0f; Z[c] = 0.0f; }
     const V *pv = reinterpret_cast<const V *>(preds);
-    for (int k = 0; k < a.K; ++k) {
-        const int32_t s = a.s[k];
-        if (x0 < s || x0 >= a.e[k]) continue;      // Eq. 14 (a vector never straddles s_k or e_k)
-        const int32_t j0 = x0 - s;                  // Eq. 13
-        const int32_t len = a.len[k], ds = a.delta_start[k], de = a.delta_end[k];
-        uint64_t idx;
-        if (X_PER_ELEM)
-            idx = uint64_t(a.off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) / VEC;
-        else
-            idx = uint64_t(a.off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) * a.inner_vec + r_in;
-        const V p = pv[idx];
-        const float *pf = reinterpret_cast<const float *>(&p);
-        if (X_PER_ELEM) {
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) {
-                const float w = ramp_weight(j0 + c, len, ds, de);
-                A[c] = __fadd_rn(A[c], __fmul_rn(w, pf[c]));   // Eq. 15: rounded product, rounded sum
-                Z[c] = __fadd_rn(Z[c], w);                      // Eq. 16
-            }
-        } else {
-            const float w = ramp_weight(j0, len, ds, de);
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) {
-                A[c] = __fadd_rn(A[c], __fmul_rn(w, pf[c]));
-                Z[c] = __fadd_rn(Z[c], w);
-            }
+    if (LANE_K) {
+        const int k_lo = x0 >= a.ovl ? int(fastdiv(uint32_t(x0 - a.ovl), a.core_div)) : 0;
+        const int k_hi = min(a.K - 1, int(fastdiv(uint32_t(x0 + a.ovl), a.core_div)));
+        for (int k = k_lo; k <= k_hi; ++k) {
+            const int32_t s = plan_s[k];
+            if (x0 < s || x0 >= plan_e[k]) continue;   // Eq. 14 (a vector never straddles s_k or e_k)
+            const int32_t j0 = x0 - s;                  // Eq. 13
+            const int32_t len = plan_len[k];
+            uint64_t idx;
+            if (X_PER_ELEM)
+                idx = uint64_t(plan_off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) / VEC;
+            else
+                idx = uint64_t(plan_off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) * a.inner_vec + r_in;
+            blend_term<VEC, X_PER_ELEM>(pv[idx], j0, len, plan_ds[k], plan_de[k], A, Z);
+        }
+    } else {
+        for (int k = 0; k < a.K; ++k) {
+            const int32_t s = a.s[k];
+            if (x0 < s || x0 >= a.e[k]) continue;
+            const int32_t j0 = x0 - s;
+            const int32_t len = a.len[k];
+            const uint64_t idx = uint64_t(a.off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) * a.inner_vec + r_in;
+            blend_term<VEC, false>(pv[idx], j0, len, a.delta_start[k], a.delta_end[k], A, Z);
         }
     }
     V res;
@@ -234,9 +277,15 @@ int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, hipStr
     const bool x_per_elem = (pl->inner % VEC) != 0;   // pick_vec allows this only for inner == 1
     a.inner_vec = x_per_elem ? 1 : uint32_t(pl->inner / VEC);
     a.inner_div = make_fastdiv(a.inner_vec);
+    const int32_t p = pl->dim == 0 ? pl->cfg.pT : pl->dim == 1 ? pl->cfg.pH : pl->cfg.pW;
+    a.core_div = make_fastdiv(uint32_t(pl->L) * uint32_t(p));
+    a.ovl = pl->O * p;
+    // a wave of 64 vectors sits on at least 64 / inner_vec different x
+    const bool lane_k = x_per_elem || a.inner_vec < 16;
     dim3 grid((a.n_vec + kThreads - 1) / kThreads);
-    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true>)
-                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false>);
+    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true, true>)
+                     : lane_k   ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, true>)
+                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, false>);
     return lp::launch_kernel(fn, grid, dim3(kThreads), 0, stream, preds, out, a);
 }
 

@@ -1,0 +1,141 @@
+"""Condense rocprofv3 CSV output of a `bench.py` run into the short tables kept under profiles/.
+
+    python -m paper_2512_07350_amd.profile_summary stats   <dir-or-csv>
+    python -m paper_2512_07350_amd.profile_summary traffic <fetch-dir> <write-dir> --workload NAME [--json OUT]
+
+`stats` reads `*_kernel_stats.csv` (from `rocprofv3 --kernel-trace --stats`) and prints one row
+per kernel of this library.  `traffic` reads the `*_counter_collection.csv` files of two
+`rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; both counters are KiB per dispatch) of
+`bench.py --copy-calibration`, scales them by what the same counter reads for the plain device
+copy of known size, and prints bytes per launch; with --json it also writes the record
+`bench.py` reads for `roofline.traffic`.  Host-side text processing only: no GPU, no oracle.
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import glob
+import json
+import os
+import re
+import sys
+
+OURS = ("attention_kernel", "combine_kernel", "partition_kernel", "reconstruct_kernel")
+COPY_KIB = 256 * 1024          # bench.py --copy-calibration copies 256 MiB
+
+
+def short(name: str) -> str:
+    """`void (anonymous namespace)::attention_kernel<128, 1>(...)` -> `attention_kernel<128,1>`."""
+    m = re.search(r"(\w+_kernel)(<[^>]*>)?", name)
+    return (m.group(1) + (m.group(2) or "")).replace(" ", "") if m else name[:60]
+
+
+def find_csv(path: str, suffix: str) -> str:
+    if os.path.isfile(path):
+        return path
+    hits = sorted(glob.glob(os.path.join(path, "**", "*" + suffix), recursive=True))
+    if not hits:
+        raise SystemExit("no *%s under %s" % (suffix, path))
+    return hits[0]
+
+
+def stats(path: str) -> None:
+    rows = list(csv.DictReader(open(find_csv(path, "kernel_stats.csv"))))
+    total = sum(float(r["TotalDurationNs"]) for r in rows)
+    print("| kernel | calls | total ms | average us | % of GPU time | min us | max us |")
+    print("|---|---|---|---|---|---|---|")
+    for r in rows:
+        if not any(k in r["Name"] for k in OURS):
+            continue
+        t = float(r["TotalDurationNs"])
+        print("| `%s` | %d | %.3f | %.2f | %.2f | %.2f | %.2f |" % (
+            short(r["Name"]), int(r["Calls"]), t / 1e6, float(r["AverageNs"]) / 1e3, 100.0 * t / total,
+            float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3))
+
+
+def counter_means(path: str, counter: str):
+    """-> {short kernel name: (dispatches, mean KiB)}, plus the copy kernel under 'copy'."""
+    acc = {}
+    for r in csv.DictReader(open(find_csv(path, "counter_collection.csv"))):
+        if r["Counter_Name"] != counter:
+            continue
+        name = r["Kernel_Name"]
+        if any(k in name for k in OURS):
+            key = short(name)
+        elif "copyBuffer" in name or "copy_buffer" in name.lower():
+            key = "copy"
+        else:
+            continue
+        n, s = acc.get(key, (0, 0.0))
+        acc[key] = (n + 1, s + float(r["Counter_Value"]))
+    return {k: (n, s / n) for k, (n, s) in acc.items()}
+
+
+def traffic(fetch_dir: str, write_dir: str, workload: str, out_json: str | None, algorithmic: float | None) -> None:
+    fetch = counter_means(fetch_dir, "FETCH_SIZE")
+    write = counter_means(write_dir, "WRITE_SIZE")
+    # Several small copies (host uploads) may share the copy kernel's name; take the maximum reading
+    # of a single dispatch instead of the mean for the calibration row.
+    def max_copy(path, counter):
+        best = 0.0
+        for r in csv.DictReader(open(find_csv(path, "counter_collection.csv"))):
+            if r["Counter_Name"] == counter and "copyBuffer" in r["Kernel_Name"]:
+                best = max(best, float(r["Counter_Value"]))
+        if best <= 0:
+            raise SystemExit("no copy dispatch found: run bench.py with --copy-calibration")
+        return best
+    f_scale = COPY_KIB / max_copy(fetch_dir, "FETCH_SIZE")
+    w_scale = COPY_KIB / max_copy(write_dir, "WRITE_SIZE")
+    print("copy of %d KiB: FETCH_SIZE scale %.4f, WRITE_SIZE scale %.4f" % (COPY_KIB, f_scale, w_scale))
+    print("| kernel | dispatches | FETCH_SIZE mean KiB | WRITE_SIZE mean KiB | scaled read MB | scaled write MB |")
+    print("|---|---|---|---|---|---|")
+    rec = {}
+    for key in sorted(set(fetch) | set(write)):
+        if key == "copy":
+            continue
+        n, f = fetch.get(key, (0, 0.0))
+        _, wv = write.get(key, (0, 0.0))
+        rb, wb = f * 1024 * f_scale, wv * 1024 * w_scale
+        rec[key] = dict(launches=n, fetch_bytes=int(rb), write_bytes=int(wb))
+        print("| `%s` | %d | %.1f | %.1f | %.2f | %.2f |" % (key, n, f, wv, rb / 1e6, wb / 1e6))
+    att = [k for k in rec if k.startswith("attention_kernel")]
+    comb = [k for k in rec if k.startswith("combine_kernel")]
+    per_call = None
+    if att:
+        a = rec[att[0]]
+        per_call = a["fetch_bytes"] + a["write_bytes"]
+        if comb:
+            c = rec[comb[0]]
+            per_call += (c["fetch_bytes"] + c["write_bytes"]) * c["launches"] / a["launches"]
+        print("per lp_attention call (attention kernel + its share of merge kernels): %.1f MB" % (per_call / 1e6))
+    if out_json:
+        doc = {"workload": workload,
+               "command": "rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --kernel-trace -- python3 bench.py --steps 3 --warmup 1 "
+                          "--no-cpu-baseline --copy-calibration",
+               "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4), "kernels": rec,
+               "attention_bytes_per_launch": int(per_call) if per_call else None,
+               "algorithmic_bytes_per_launch": algorithmic}
+        with open(out_json, "w") as fh:
+            json.dump(doc, fh, indent=1)
+            fh.write("\n")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    s = sub.add_parser("stats"); s.add_argument("path")
+    t = sub.add_parser("traffic")
+    t.add_argument("fetch_dir"); t.add_argument("write_dir")
+    t.add_argument("--workload", required=True)
+    t.add_argument("--json", default=None)
+    t.add_argument("--algorithmic-bytes", type=float, default=None)
+    a = ap.parse_args()
+    if a.cmd == "stats":
+        stats(a.path)
+    else:
+        traffic(a.fetch_dir, a.write_dir, a.workload, a.json, a.algorithmic_bytes)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
