@@ -155,7 +155,7 @@ int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n
 
 /*
  * Bytes of workspace lp_attention can use on the current device for this
- * head_dim (2 partial-result slots per compute unit; about 68 MB for head_dim
+ * head_dim (2 partial-result slots per compute unit; about 35 MB for head_dim
  * 128 on 256 compute units).  Negative LP_ERR_* on failure.
  */
 int64_t lp_attention_workspace_size(int32_t head_dim);

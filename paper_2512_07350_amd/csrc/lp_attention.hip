@@ -346,10 +346,11 @@ struct AttnParams {
     uint32_t shared_wgs;       // workgroups 0 .. shared_wgs-1 (logical order) take part in the shared space
 };
 
-// A slot holds, for the 256 query rows of a unit: m[256], l[256], then the unnormalised
-// O rows [256][D], all binary32.
+// A slot holds, for the 256 query rows of a unit: m[256] and l[256] in binary32, then the
+// unnormalised O rows [256][D] rounded to bf16 (the merged row is rounded to bf16 on store
+// anyway; halving the rows halves the traffic of the merge).
 template <int D>
-constexpr int slot_floats() { return kBM * (D + 2); }
+constexpr int slot_floats() { return kBM * (D / 2 + 2); }
 
 // First iteration of (logical) workgroup p when W iterations are dealt to P workgroups.
 __device__ __forceinline__ uint32_t range_start(uint32_t p, uint32_t W, uint32_t P) {
@@ -581,14 +582,16 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                     slot[row] = -w.neg_m[nb][0];
                     slot[kBM + row] = l_tot;
                 }
-                float *arow = slot + 2 * kBM + row * D;
+                __bf16 *arow = reinterpret_cast<__bf16 *>(slot + 2 * kBM) + row * D;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g)
-                        *reinterpret_cast<float4 *>(arow + mb * 32 + g * 8 + half * 4) =
-                            make_float4(w.acc[mb][nb][4 * g + 0], w.acc[mb][nb][4 * g + 1],
-                                        w.acc[mb][nb][4 * g + 2], w.acc[mb][nb][4 * g + 3]);
+                    for (int g = 0; g < 4; ++g) {
+                        union { uint2 u; bf16x2 p[2]; } ow;
+                        ow.p[0] = to_bf16x2(w.acc[mb][nb][4 * g + 0], w.acc[mb][nb][4 * g + 1]);
+                        ow.p[1] = to_bf16x2(w.acc[mb][nb][4 * g + 2], w.acc[mb][nb][4 * g + 3]);
+                        *reinterpret_cast<uint2 *>(arow + mb * 32 + g * 8 + half * 4) = ow.u;
+                    }
             }
         }
         first_segment = false;
@@ -626,14 +629,16 @@ __global__ __launch_bounds__(32 * (D / 16)) void combine_kernel(const AttnParams
         const float *slot = p == pf ? slot0 : first_later + (p - pf - 1) * slot_step;
         const float f = __builtin_amdgcn_exp2f(slot[row] - m);
         l += slot[kBM + row] * f;
-        const float4 *src = reinterpret_cast<const float4 *>(slot + 2 * kBM + row * D + ch * 16);
+        const uint4 *src = reinterpret_cast<const uint4 *>(reinterpret_cast<const __bf16 *>(slot + 2 * kBM) + row * D + ch * 16);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float4 x = src[e];
-            acc[4 * e + 0] += x.x * f;
-            acc[4 * e + 1] += x.y * f;
-            acc[4 * e + 2] += x.z * f;
-            acc[4 * e + 3] += x.w * f;
+        for (int e = 0; e < 2; ++e) {
+            const uint4 x = src[e];
+            const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {     // a bf16 is the upper half of the binary32 of the same value
+                acc[8 * e + 2 * j + 0] += __uint_as_float(wds[j] << 16) * f;
+                acc[8 * e + 2 * j + 1] += __uint_as_float(wds[j] & 0xffff0000u) * f;
+            }
         }
     }
     const float inv = 1.0f / l;
