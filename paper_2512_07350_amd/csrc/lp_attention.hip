@@ -4,8 +4,8 @@
 // gfx950: bf16 MFMA 32x32x16 for both products, binary32 online softmax, K and V
 // tiles streamed global -> LDS without passing through registers.
 //
-// Work decomposition.  One workgroup = 4 wavefronts = 256 query rows of one head;
-// each wavefront owns 64 query rows (two 32-column MFMA blocks) and walks all keys
+// Work decomposition.  One workgroup = 8 wavefronts = 256 query rows of one head;
+// each wavefront owns 32 query rows (one 32-column MFMA block) and walks all keys
 // in rounds of 32.  Per round it forms the TRANSPOSED scores
 //     S^T[key, query] = K . Q^T            (A = K rows from LDS, B = Q in registers)
 // so that in the MFMA accumulator layout a lane holds 16 scores of ONE query: the
@@ -41,6 +41,8 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 #define LP_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 
@@ -59,7 +61,9 @@ struct Tile {
     static constexpr int kGran = kRowBytes / 16;            // 16-byte granules per row
     static constexpr int kTileBytes = kBN * kRowBytes;      // one K or one V tile
     static constexpr int kStageBytes = 2 * kTileBytes;      // K tile then V tile
-    static constexpr int kBytes = kStages * kStageBytes;
+    static constexpr int kRingBytes = kStages * kStageBytes;
+    static constexpr int kOutBytes = 4096;                  // per wave: 32 result rows of 64 d in bf16
+    static constexpr int kBytes = kRingBytes + kWaves * kOutBytes;
     static constexpr int kRowsPerInstr = 1024 / kRowBytes;  // rows one wave-wide 16-byte load covers
     static constexpr int kInstrPerTile = kBN / kRowsPerInstr;
     static constexpr int kLoadsPerWave = 2 * kInstrPerTile / kWaves;   // K and V, per tile
@@ -92,6 +96,12 @@ __device__ __forceinline__ void wait_tile_loads() {
 }
 
 // LDS accesses below use 32-bit LDS byte addresses held in registers.
+// The same value, but not a loop invariant as far as the compiler can tell.
+__device__ __forceinline__ int opaque(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 template <typename V>
 __device__ __forceinline__ V lds_load(uint32_t addr) {
     return *LP_LDS_PTR(const V, uintptr_t(addr));
@@ -254,6 +264,36 @@ struct Pipe {
     int issue_t;                   // index of the next tile to issue
 };
 
+// Writes this wave's 32 result rows (acc scaled by `inv`, rounded to bf16) to rows
+// dst + r * row_stride, r < rows_valid.  A lane holds, for query `col`, rows
+// d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T, i.e. 8-byte pieces of many rows; the pieces
+// pass through the wave's own 4 KB of LDS (64 d at a time, 16-byte granules XORed with
+// the row so that both directions are conflict free) and leave as whole 128-byte lines.
+template <int D>
+__device__ __forceinline__ void store_rows(uint32_t out_lds, const f32x16 (&acc)[D / 32][1], float inv, __bf16 *dst,
+                                           int64_t row_stride, int rows_valid, int lane) {
+    const int col = lane % 32, half = lane / 32;
+#pragma unroll
+    for (int pass = 0; pass < D / 64; ++pass) {
+#pragma unroll
+        for (int mbl = 0; mbl < 2; ++mbl)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x16 &x = acc[2 * pass + mbl][0];
+                union { u32x2 u; bf16x2 p[2]; } ow;
+                ow.p[0] = to_bf16x2(x[4 * g + 0] * inv, x[4 * g + 1] * inv);
+                ow.p[1] = to_bf16x2(x[4 * g + 2] * inv, x[4 * g + 3] * inv);
+                *LP_LDS_PTR(u32x2, uintptr_t(out_lds + col * 128 + 16 * ((4 * mbl + g) ^ (col & 7)) + 8 * half)) = ow.u;
+            }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = lane / 8 + 8 * j, gran = lane % 8;
+            const u32x4 u = lds_load<u32x4>(out_lds + r * 128 + 16 * (gran ^ (r & 7)));
+            if (r < rows_valid) *reinterpret_cast<u32x4 *>(dst + r * row_stride + 64 * pass + 8 * gran) = u;
+        }
+    }
+}
+
 template <int BYTES>
 __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
     off += BYTES;
@@ -365,6 +405,90 @@ __device__ __forceinline__ uint32_t logical_workgroup(uint32_t b, uint32_t n_wg)
     return xcd * base + (xcd < rem ? xcd : rem) + slot;
 }
 
+// A segment: the tiles [t_begin, t_stop) of one unit.
+struct Segment {
+    uint32_t unit;
+    int t_begin, t_stop;
+    bool valid;
+};
+
+// Where a workgroup stands in its work: its range of the shared space first, then whole units.
+struct Walk {
+    uint32_t it, it_end;
+    int whole_round;
+};
+
+__device__ __forceinline__ Segment next_segment(Walk &k, const AttnParams &a, uint32_t tpu, uint32_t lp, uint32_t n_wg) {
+    Segment s;
+    s.valid = true;
+    if (k.it < k.it_end) {
+        s.unit = k.it / tpu;
+        s.t_begin = int(k.it - s.unit * tpu);
+        s.t_stop = int(min(tpu, uint32_t(s.t_begin) + (k.it_end - k.it)));
+        k.it += uint32_t(s.t_stop - s.t_begin);
+    } else if (k.whole_round < a.whole_rounds) {
+        s.unit = uint32_t(a.shared_units) + uint32_t(k.whole_round) * n_wg + lp;
+        s.t_begin = 0;
+        s.t_stop = int(tpu);
+        ++k.whole_round;
+    } else {
+        s.unit = 0;
+        s.t_begin = s.t_stop = 0;
+        s.valid = false;
+    }
+    return s;
+}
+
+// Points the tile traffic at a segment and sends for its first kStages-2 tiles (the
+// segment's tiles use the LDS stages in turn, from stage 0).  The caller has made sure
+// that no wave still reads the stages.
+template <int D, int NB>
+__device__ __forceinline__ void start_tiles(unsigned char *smem, const AttnParams &a, const Segment &seg,
+                                            Lane<D, NB> &c, Pipe<D, NB> &w, int n, int64_t stride_tok) {
+    using T = Tile<D, NB>;
+    const int head = int(seg.unit) / a.n_qtiles;
+    const int64_t head_off = int64_t(head) * a.stride_head;
+    c.key_end = min(n, seg.t_stop * kBN);
+    c.t_end = seg.t_stop;
+    {
+        // raw buffers over this head's K and V, ending with the last element of token n-1
+        // (flags: 32-bit data format, as every untyped buffer on this architecture)
+        const int valid_bytes = int((int64_t(n - 1) * stride_tok + D) * 2);
+        const __bf16 *kh = a.k + head_off, *vh = a.v + head_off;
+        c.k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(kh), 0, valid_bytes, 0x00020000);
+        c.v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(vh), 0, valid_bytes, 0x00020000);
+    }
+    w.issue_off = 0;
+    w.issue_t = seg.t_begin;
+#pragma unroll
+    for (int t = 0; t < kStages - 2; ++t) {
+        if (w.issue_t < c.t_end) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
+        w.issue_off += T::kStageBytes;
+        ++w.issue_t;
+    }
+}
+
+// Loads a segment's raw Q rows: a lane holds, for query `col`, d = 16*kk + 8*half .. +7.
+template <int D, int NB>
+__device__ __forceinline__ void load_q(const AttnParams &a, const Segment &seg, Pipe<D, NB> &w, int n,
+                                       int64_t stride_tok, int wave, int col, int half) {
+    const int head = int(seg.unit) / a.n_qtiles;
+    const int qtile = int(seg.unit) % a.n_qtiles;
+    const __bf16 *qh = a.q + int64_t(head) * a.stride_head;
+    const int q0 = qtile * kBM + wave * (32 * NB);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int qi = q0 + nb * 32 + col;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+            Pack16 t;
+            t.u = make_uint4(0, 0, 0, 0);
+            if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + half * 8);
+            w.qreg[nb][kk] = t.v;
+        }
+    }
+}
+
 template <int D, int NB>
 __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const AttnParams a) {
     using T = Tile<D, NB>;
@@ -376,7 +500,8 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-    const int lane = tid % 64;
+    const int lane_id = tid % 64;
+    const int lane = lane_id;
     const int col = lane % 32;        // MFMA column (query) / A-operand row
     const int half = lane / 32;
     const int n = a.n;
@@ -400,70 +525,34 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
     // ---- this workgroup's range of the shared (unit, tile) space, then its whole units
     const uint32_t lp = logical_workgroup(blockIdx.x, gridDim.x);
     const bool sharing = lp < a.shared_wgs;
-    uint32_t it = sharing ? range_start(lp, a.shared_work, a.shared_wgs) : 0u;
-    const uint32_t it_end = sharing ? range_start(lp + 1, a.shared_work, a.shared_wgs) : 0u;
     const uint32_t tpu = uint32_t(a.tiles_per_unit);
-    int whole_round = 0;
+    Walk walk;
+    walk.it = sharing ? range_start(lp, a.shared_work, a.shared_wgs) : 0u;
+    walk.it_end = sharing ? range_start(lp + 1, a.shared_work, a.shared_wgs) : 0u;
+    walk.whole_round = 0;
+    const uint32_t out_lds = lds0 + T::kRingBytes + wave * T::kOutBytes;
     bool first_segment = true;
 
-    while (true) {
-        uint32_t unit;
-        int t_begin, t_stop;
-        if (it < it_end) {
-            unit = it / tpu;
-            t_begin = int(it - unit * tpu);
-            t_stop = int(min(tpu, uint32_t(t_begin) + (it_end - it)));
-            it += uint32_t(t_stop - t_begin);
-        } else if (whole_round < a.whole_rounds) {
-            unit = uint32_t(a.shared_units) + uint32_t(whole_round) * gridDim.x + lp;
-            t_begin = 0;
-            t_stop = int(tpu);
-            ++whole_round;
-        } else {
-            break;
-        }
-        const int head = int(unit) / a.n_qtiles;
-        const int qtile = int(unit) % a.n_qtiles;
-        const int64_t head_off = int64_t(head) * a.stride_head;
-        const __bf16 *qh = a.q + head_off;
+    Segment seg = next_segment(walk, a, tpu, lp, gridDim.x);
+    if (!seg.valid) return;
+    Pipe<D, NB> w;
+    start_tiles<D, NB>(smem, a, seg, c, w, n, stride_tok);
+    load_q<D, NB>(a, seg, w, n, stride_tok, wave, col, half);
 
+    while (true) {
+        const int qtile = int(seg.unit) % a.n_qtiles;
+        const int64_t head_off = int64_t(int(seg.unit) / a.n_qtiles) * a.stride_head;
+        const int t_begin = seg.t_begin, t_stop = seg.t_stop;
         const int i_begin = 2 * t_begin;                 // rounds [i_begin, i_end) of 32 keys
         const int i_end = min(2 * t_stop, n_rounds);
-        c.key_end = min(n, t_stop * kBN);
-        c.t_end = t_stop;
-        {
-            // raw buffers over this head's K and V, ending with the last element of token n-1
-            // (flags: 32-bit data format, as every untyped buffer on this architecture)
-            const int valid_bytes = int((int64_t(n - 1) * stride_tok + D) * 2);
-            c.k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(a.k + head_off), 0, valid_bytes, 0x00020000);
-            c.v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(a.v + head_off), 0, valid_bytes, 0x00020000);
-        }
 
-        // every wave has left the previous segment's tiles before their stages are refilled
-        __syncthreads();
-
-        // stage s lives at byte offset s * kStageBytes; the segment's tiles use the stages in turn
-        Pipe<D, NB> w;
-        w.issue_off = 0;
-        w.issue_t = t_begin;
+        // ---- Q^T operands arrive raw; multiply by scale*log2(e) and round to bf16 again
 #pragma unroll
-        for (int t = 0; t < kStages - 2; ++t) {
-            if (w.issue_t < c.t_end) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
-            w.issue_off += T::kStageBytes;
-            ++w.issue_t;
-        }
-
-        // ---- Q^T operands, pre-multiplied by scale*log2(e): lane holds, for query `col`
-        // of block nb, d = 16*kk + 8*half .. +7
-        const int q0 = qtile * kBM + wave * (32 * NB);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int qi = q0 + nb * 32 + col;
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
                 Pack16 t;
-                t.u = make_uint4(0, 0, 0, 0);
-                if (qi < n) t.u = *reinterpret_cast<const uint4 *>(qh + int64_t(qi) * stride_tok + kk * 16 + half * 8);
+                t.v = w.qreg[nb][kk];
                 const uint32_t u[4] = {t.u.x, t.u.y, t.u.z, t.u.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e)   // a bf16 is the upper half of the binary32 with the same value
@@ -471,7 +560,6 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                                        __uint_as_float(u[e] & 0xffff0000u) * a.scale_log2e);
                 w.qreg[nb][kk] = t.v;
             }
-        }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -481,11 +569,13 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) w.l_run[nb] = 0.0f;
 
-        // ---- LDS operand addresses in stage 0
+        // ---- LDS operand addresses in stage 0 (recomputed from an opaque copy of the lane
+        // index: kept as loop invariants they would be held in registers through the pipeline)
         w.tile_off = 0;
         w.k_off = 0;
         w.v_off = 0;
         {
+            const int lane = opaque(lane_id), col = lane % 32, half = lane / 32;
             // K operand: row = col with bits 2 and 3 swapped, so that accumulator register i
             // of a lane is key 16*(i/8) + 8*half + i%8 of the round
             const int krow = (col & 0x13) | ((col & 4) << 1) | ((col & 8) >> 1);
@@ -548,53 +638,36 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
             pipeline_step<D, NB, 1, true>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
         }
 
-        // ---- results.  A lane holds, for query `col` of block nb, rows
-        // d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T.
+        // ---- the next segment's first tiles set out before this segment's results are
+        // stored, so that their latency hides behind the stores
+        const Segment nxt = next_segment(walk, a, tpu, lp, gridDim.x);
+        if (nxt.valid) {
+            __syncthreads();        // every wave has left this segment's tiles before their stages are refilled
+            start_tiles<D, NB>(smem, a, nxt, c, w, n, stride_tok);
+        }
+
+        // ---- results of this segment: final rows, or (a unit shared with other workgroups)
+        // running maximum, row sum and unnormalised rows into this workgroup's slot
+        static_assert(NB == 1, "store_rows handles one 32-row block per wave");
+        const int lane = opaque(lane_id), col = lane % 32, half = lane / 32;
         const bool whole = (t_begin == 0) && (uint32_t(t_stop) == tpu);
+        const float l_tot = w.l_run[0] + other_half(w.l_run[0]);
+        const int row0 = wave * 32;
         if (whole) {
-            __bf16 *oh = a.o + head_off;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
-                const float inv = 1.0f / l_tot;
-                const int qi = q0 + nb * 32 + col;
-                if (qi < n) {
-                    __bf16 *orow = oh + int64_t(qi) * stride_tok;
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            union { uint2 u; bf16x2 p[2]; } ow;
-                            ow.p[0] = to_bf16x2(w.acc[mb][nb][4 * g + 0] * inv, w.acc[mb][nb][4 * g + 1] * inv);
-                            ow.p[1] = to_bf16x2(w.acc[mb][nb][4 * g + 2] * inv, w.acc[mb][nb][4 * g + 3] * inv);
-                            *reinterpret_cast<uint2 *>(orow + mb * 32 + g * 8 + half * 4) = ow.u;
-                        }
-                }
-            }
+            const int q0 = qtile * kBM + row0;
+            store_rows<D>(out_lds, w.acc, 1.0f / l_tot, a.o + head_off + int64_t(q0) * stride_tok, stride_tok, n - q0, lane);
         } else {
-            // partial: running maximum, row sum and unnormalised rows into this workgroup's slot
             float *slot = a.ws + (size_t(2) * lp + (first_segment ? 0 : 1)) * slot_floats<D>();
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
-                const int row = wave * (32 * NB) + nb * 32 + col;
-                if (half == 0) {
-                    slot[row] = -w.neg_m[nb][0];
-                    slot[kBM + row] = l_tot;
-                }
-                __bf16 *arow = reinterpret_cast<__bf16 *>(slot + 2 * kBM) + row * D;
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        union { uint2 u; bf16x2 p[2]; } ow;
-                        ow.p[0] = to_bf16x2(w.acc[mb][nb][4 * g + 0], w.acc[mb][nb][4 * g + 1]);
-                        ow.p[1] = to_bf16x2(w.acc[mb][nb][4 * g + 2], w.acc[mb][nb][4 * g + 3]);
-                        *reinterpret_cast<uint2 *>(arow + mb * 32 + g * 8 + half * 4) = ow.u;
-                    }
+            if (half == 0) {
+                slot[row0 + col] = -w.neg_m[0][0];
+                slot[kBM + row0 + col] = l_tot;
             }
+            store_rows<D>(out_lds, w.acc, 1.0f, reinterpret_cast<__bf16 *>(slot + 2 * kBM) + row0 * D, D, 32, lane);
         }
         first_segment = false;
+        if (!nxt.valid) break;
+        seg = nxt;
+        load_q<D, NB>(a, seg, w, n, stride_tok, wave, col, half);   // (this block's opaque col, half)
     }
 }
 
