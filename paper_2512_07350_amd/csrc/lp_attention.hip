@@ -53,6 +53,7 @@ constexpr int kBlocksPerWave = 1;             // NB used by lp_attention
 constexpr int kBN = 64;                       // keys per LDS tile (two rounds of 32)
 constexpr int kStages = 4;                    // LDS stages: three tiles in use plus one arriving
 constexpr float kRescaleThreshold = 8.0f;     // log2 units the running max may lag behind
+constexpr uint32_t kBoundaryTiles = 3;        // what changing units costs a workgroup, in tile times
 
 template <int D, int NB>
 struct Tile {
@@ -366,10 +367,14 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D,
 
 // Launch parameters.  A unit is one 256-row query tile of one head; every unit walks
 // tiles_per_unit tiles of 64 keys.  With P workgroups, the units are served in two parts:
-//  * the first shared_units units form a (unit, key tile) iteration space of
-//    shared_work = shared_units * tiles_per_unit tiles that is cut into shared_wgs <= P equal
-//    contiguous ranges (never empty), so a workgroup may start and end in the middle of a
-//    unit; such partial results go to `ws` and are merged by combine_kernel;
+//  * the first shared_units units form a (unit, key tile) iteration space that is cut into
+//    shared_wgs <= P contiguous ranges (never empty), so a workgroup may start and end in
+//    the middle of a unit; such partial results go to `ws` and are merged by combine_kernel.
+//    The cut is even in COST, not in tiles: every unit is preceded by kBoundaryTiles
+//    imaginary tiles that stand for what a workgroup pays to change units (drain and
+//    refill of the pipeline, stores, a new Q), the space of shared_units * unit_cost
+//    real and imaginary tiles is cut into equal ranges, and a range's imaginary tiles are
+//    dropped.  A workgroup that changes units thus gets fewer tiles than one that does not.
 //  * the remaining whole_rounds * P units are taken whole, unit shared_units + r*P + p by
 //    workgroup p in round r: the workgroups of an XCD then walk the keys of one head in
 //    step and share its K/V stream through the L2.
@@ -382,7 +387,8 @@ struct AttnParams {
     float scale_log2e;
     int n, n_qtiles, tiles_per_unit;
     int shared_units, whole_rounds;
-    uint32_t shared_work;      // shared_units * tiles_per_unit
+    uint32_t shared_work;      // shared_units * unit_cost
+    uint32_t unit_cost;        // tiles_per_unit + kBoundaryTiles
     uint32_t shared_wgs;       // workgroups 0 .. shared_wgs-1 (logical order) take part in the shared space
 };
 
@@ -395,6 +401,12 @@ constexpr int slot_floats() { return kBM * (D / 2 + 2); }
 // First iteration of (logical) workgroup p when W iterations are dealt to P workgroups.
 __device__ __forceinline__ uint32_t range_start(uint32_t p, uint32_t W, uint32_t P) {
     return uint32_t(uint64_t(p) * W / P);
+}
+
+// Position x in the space with imaginary tiles -> index of the first real tile at or after it.
+__device__ __forceinline__ uint32_t real_tile(uint32_t x, uint32_t unit_cost, uint32_t tpu) {
+    const uint32_t unit = x / unit_cost, r = x - unit * unit_cost, imaginary = unit_cost - tpu;
+    return unit * tpu + (r > imaginary ? r - imaginary : 0u);
 }
 
 // Workgroup ids are dealt round robin to the 8 XCDs; remap so that each XCD owns a
@@ -527,8 +539,8 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
     const bool sharing = lp < a.shared_wgs;
     const uint32_t tpu = uint32_t(a.tiles_per_unit);
     Walk walk;
-    walk.it = sharing ? range_start(lp, a.shared_work, a.shared_wgs) : 0u;
-    walk.it_end = sharing ? range_start(lp + 1, a.shared_work, a.shared_wgs) : 0u;
+    walk.it = sharing ? real_tile(range_start(lp, a.shared_work, a.shared_wgs), a.unit_cost, tpu) : 0u;
+    walk.it_end = sharing ? real_tile(range_start(lp + 1, a.shared_work, a.shared_wgs), a.unit_cost, tpu) : 0u;
     walk.whole_round = 0;
     const uint32_t out_lds = lds0 + T::kRingBytes + wave * T::kOutBytes;
     bool first_segment = true;
@@ -644,6 +656,7 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         if (nxt.valid) {
             __syncthreads();        // every wave has left this segment's tiles before their stages are refilled
             start_tiles<D, NB>(smem, a, nxt, c, w, n, stride_tok);
+            load_q<D, NB>(a, nxt, w, n, stride_tok, wave, opaque(lane_id) % 32, opaque(lane_id) / 32);
         }
 
         // ---- results of this segment: final rows, or (a unit shared with other workgroups)
@@ -667,7 +680,6 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         first_segment = false;
         if (!nxt.valid) break;
         seg = nxt;
-        load_q<D, NB>(a, seg, w, n, stride_tok, wave, col, half);   // (this block's opaque col, half)
     }
 }
 
@@ -680,17 +692,19 @@ __global__ __launch_bounds__(32 * (D / 16)) void combine_kernel(const AttnParams
     constexpr int kChunks = D / 16;
     const uint32_t unit = blockIdx.x;
     const uint32_t W = a.shared_work, tpu = uint32_t(a.tiles_per_unit);
-    const uint32_t lo = unit * tpu, hi = lo + tpu;            // the unit's iterations in the shared space
-    // workgroup holding iteration x: the largest p with range_start(p) <= x
-    const uint32_t pf = uint32_t((uint64_t(lo + 1) * n_wg - 1) / W);
-    const uint32_t pl = uint32_t((uint64_t(hi) * n_wg - 1) / W);
+    // the unit's real tiles sit at [x_lo, x_hi) of the shared space, after its imaginary ones
+    const uint32_t x_hi = (unit + 1) * a.unit_cost, x_lo = x_hi - tpu;
+    // workgroup holding position x: the largest p with range_start(p) <= x
+    const uint32_t pf = uint32_t((uint64_t(x_lo + 1) * n_wg - 1) / W);
+    const uint32_t pl = uint32_t((uint64_t(x_hi) * n_wg - 1) / W);
     if (pf == pl) return;                                      // computed whole by one workgroup
     const int head = int(unit) / a.n_qtiles, qtile = int(unit) % a.n_qtiles;
     const int row = int(blockIdx.y) * 32 + int(threadIdx.x) / kChunks, ch = int(threadIdx.x) % kChunks;
     const int qi = qtile * kBM + row;
     if (qi >= a.n) return;
     // a workgroup's first segment lies in slot 0, a later (its last) one in slot 1
-    const float *slot0 = a.ws + (size_t(2) * pf + (range_start(pf, W, n_wg) >= lo ? 0 : 1)) * slot_floats<D>();
+    const bool pf_starts_here = range_start(pf, W, n_wg) >= unit * a.unit_cost;
+    const float *slot0 = a.ws + (size_t(2) * pf + (pf_starts_here ? 0 : 1)) * slot_floats<D>();
     const size_t slot_step = size_t(2) * slot_floats<D>();    // every later workgroup starts inside the unit: slot 0
     const float *first_later = a.ws + size_t(2) * (pf + 1) * slot_floats<D>();
     float m = slot0[row];
@@ -761,6 +775,7 @@ int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hi
     a.shared_units = 0;
     a.whole_rounds = 1;
     a.shared_work = 0;
+    a.unit_cost = tpu;
     a.shared_wgs = 0;
     const int cus = device_compute_units();
     if (workspace != nullptr && cus > 0 && workspace_bytes >= workspace_bytes_for<D>(cus)) {
@@ -770,6 +785,7 @@ int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hi
         // ends inside a unit pays a second prologue and a partial store, and the merge kernel
         // follows.
         constexpr uint32_t kMinTiles = 8, kSplitCost = 6, kMergeCost = 3;
+        static_assert(kBoundaryTiles < kMinTiles, "a range of kMinTiles positions must hold a real tile");
         const uint32_t p = units < uint32_t(cus) ? units : uint32_t(cus);     // workgroups
         const uint32_t rounds = units >= uint32_t(cus) ? units / p : 0;       // whole-unit rounds
         const uint32_t shared = units - rounds * p;
@@ -786,7 +802,8 @@ int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hi
                     a.ws = static_cast<float *>(workspace);
                     a.shared_units = int(shared);
                     a.whole_rounds = int(rounds);
-                    a.shared_work = shared * tpu;
+                    a.unit_cost = tpu + kBoundaryTiles;
+                    a.shared_work = shared * a.unit_cost;
                     a.shared_wgs = sharers;
                 }
             }
@@ -826,7 +843,7 @@ extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o
     // 32-bit addressing inside one head: byte offsets below 2^31, work items below 2^31
     if (n_tokens > (int64_t(1) << 24) || (n_tokens * stride_tok + head_dim) * 2 >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
     const int64_t units = int64_t(heads) * ((n_tokens + kBM - 1) / kBM);
-    if (units * ((n_tokens + kBN - 1) / kBN) >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
+    if (units * ((n_tokens + kBN - 1) / kBN + kBoundaryTiles) >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
     if (!(scale > 0.0f)) scale = 1.0f / sqrtf(float(head_dim));
     AttnParams a{};
     a.q = static_cast<const __bf16 *>(q);
