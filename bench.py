@@ -144,7 +144,7 @@ def main() -> int:
             att_launches += 1
             d["ms"] += t; d["flops"] += flops_of(n); d["launches"] += 1
 
-    latent_cold = cold_latent_ops(lp, torch, state, w, z, stream) if args.steps > 0 else None
+    latent_dims = latent_per_dim(lp, torch, state, w, z, stream, synth)
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -176,8 +176,9 @@ def main() -> int:
                      "launches": att_launches, "avg_launch_ms": round(att_ms / max(att_launches, 1), 5),
                      "avg_flops_per_launch": att_flops / max(att_launches, 1),
                      "per_dim_tflops": {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) for k, v in per_dim.items()}},
-        "latent_ops": {"bound": "hbm", "peak": PEAK_HBM_GBPS, "unit": "GB/s", "cache": "warm (buffers reused every step)",
-                       "cold": latent_cold,
+        "latent_ops": {"bound": "hbm", "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                       "in_step": "partition / reconstruct as timed inside the steps (buffers reused every step: warm)",
+                       "per_dim": latent_dims,
                        "partition": {"GBps": round(part_bytes / (part_ms * 1e-3) / 1e9, 1), "avg_us": round(part_ms * 1e3 / args.steps, 2),
                                      "frac": round(part_bytes / (part_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)},
                        "reconstruct": {"GBps": round(rec_bytes / (rec_ms * 1e-3) / 1e9, 1), "avg_us": round(rec_ms * 1e3 / args.steps, 2),
@@ -192,93 +193,103 @@ def main() -> int:
     return 0
 
 
-def cold_latent_ops(lp, torch, state, w, z, stream, total_bytes=3 << 30, reps=3):
-    """lp_partition and lp_reconstruct of the first dim's plan with operands that come from HBM:
-    each call works on its own copy of the buffers and the copies together (about total_bytes)
-    are several times the last-level cache, so no call finds its operands cached."""
-    st = state[w.dims[0]]
-    plan = st["plan"]
-    s_ext, s_z = 4 * plan.total_elems, 4 * plan.latent_elems
-    copies = max(2, min(512, total_bytes // (2 * (s_ext + s_z))))
-    zs = [z.clone() for _ in range(copies)]
-    subs = [torch.empty_like(st["subs"]) for _ in range(copies)]
-    preds = [st["preds"].clone() for _ in range(copies)]
-    outs = [torch.empty_like(z) for _ in range(copies)]
+def latent_per_dim(lp, torch, state, w, z, stream, synth, total_bytes=2 << 30, reps=3):
+    """lp_partition and lp_reconstruct per partition dimension, each timed as a run of launches
+    back to back between two HIP events.  "warm": every call on the same buffers (operands in L2 / Infinity Cache).  "cold": each
+    call on its own copy of the buffers, the copies together (about total_bytes) several times the
+    last-level cache, so that operands come from HBM."""
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    best = {}
-    for _ in range(reps):
-        marks = []
-        for c in range(copies):
-            a = ev(); a.record()
-            lp.lp_partition(plan, zs[c], subs[c], stream)
-            b = ev(); b.record()
-            marks.append((a, b))
-        torch.cuda.synchronize()
-        t_part = sum(a.elapsed_time(b) for a, b in marks) / copies
-        marks = []
-        for c in range(copies):
-            a = ev(); a.record()
-            lp.lp_reconstruct(plan, preds[c], outs[c], stream)
-            b = ev(); b.record()
-            marks.append((a, b))
-        torch.cuda.synchronize()
-        t_rec = sum(a.elapsed_time(b) for a, b in marks) / copies
-        best["partition"] = min(best.get("partition", 1e9), t_part)
-        best["reconstruct"] = min(best.get("reconstruct", 1e9), t_rec)
-    nbytes = {"partition": 2.0 * s_ext, "reconstruct": float(s_ext + s_z)}
-    res = {"copies": int(copies), "dim": w.dims[0]}
-    for name in ("partition", "reconstruct"):
-        gbps = nbytes[name] / (best[name] * 1e-3) / 1e9
-        res[name] = {"GBps": round(gbps, 1), "avg_us": round(best[name] * 1e3, 2), "frac": round(gbps / PEAK_HBM_GBPS, 4)}
+
+    def timed(fn, n):             # n launches back to back between one pair of events
+        best = 1e9
+        for _ in range(reps):
+            a, b = ev(), ev()
+            a.record()
+            for c in range(n):
+                fn(c)
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b) / n)
+        return best
+
+    res = {}
+    for dim in sorted(state):
+        st = state[dim]
+        plan = st["plan"]
+        s_ext, s_z = 4 * plan.total_elems, 4 * plan.latent_elems
+        copies = int(max(2, min(256, total_bytes // (2 * (s_ext + s_z)))))
+        zs = [z.clone() for _ in range(copies)]
+        subs = [torch.empty_like(st["subs"]) for _ in range(copies)]
+        preds = [st["preds"].clone() for _ in range(copies)]
+        outs = [torch.empty_like(z) for _ in range(copies)]
+        t = {"warm": {"partition": timed(lambda c: lp.lp_partition(plan, zs[0], subs[0], stream), 50),
+                      "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[0], outs[0], stream), 50)},
+             "cold": {"partition": timed(lambda c: lp.lp_partition(plan, zs[c], subs[c], stream), copies),
+                      "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[c], outs[c], stream), copies)}}
+        nbytes = {"partition": 2.0 * s_ext, "reconstruct": float(s_ext + s_z)}
+        entry = {"gamma": round(s_ext / s_z, 4), "copies": copies}
+        for cache in ("warm", "cold"):
+            entry[cache] = {}
+            for name in ("partition", "reconstruct"):
+                gbps = nbytes[name] / (t[cache][name] * 1e-3) / 1e9
+                entry[cache][name] = {"us": round(t[cache][name] * 1e3, 2), "GBps": round(gbps, 1),
+                                      "frac": round(gbps / PEAK_HBM_GBPS, 4)}
+        res[synth.DIM_NAMES[dim]] = entry
+        del zs, subs, preds, outs
     return res
 
 
 def cpu_baseline(w, cfg, state, synth, np, torch):
-    """Time the CPU oracle, as it stands, on a bounded sample of this workload: the first
-    dim's step with partition and reconstruct in full and attention on every `stride`-th
-    query row of every partition (each row over all keys).  Also compares the GPU's
-    attention output on those rows with the oracle's."""
+    """Time the CPU oracle, as it stands, on a bounded sample of this workload: one step along
+    every partition dimension the workload visits, partition and reconstruct in full and attention
+    on every `stride`-th query row of every partition (each row over all keys).  Also compares
+    the GPU's attention output on those rows with the oracle's."""
     from oracle import lp_oracle as orc
-    dim = w.dims[0]
-    st = state[dim]
-    ref_plan = orc.plan(w.latent, w.patch, w.K, dim, overlap_patches=w.overlap_patches)
-    total_flops = sum(4.0 * p.n_tokens ** 2 * w.head_dim * w.heads for p in ref_plan.parts)
-    budget_flops = 2.0e12                     # 10-20 s of oracle work on 16 cores
+    dims = sorted(state)
+    plans = {d: orc.plan(w.latent, w.patch, w.K, d, overlap_patches=w.overlap_patches) for d in dims}
+    total_flops = sum(4.0 * p.n_tokens ** 2 * w.head_dim * w.heads for d in dims for p in plans[d].parts)
+    budget_flops = 2.5e12                     # 15-20 s of oracle work on 16 cores
     stride = max(1, int(np.ceil(total_flops / budget_flops)))
     z_h = synth.latent(synth.seed_for(cfg, 0, 0, tensor=9), w.latent)
-    preds_h = st["preds"].cpu().numpy()
-    t0 = time.perf_counter()
-    subs_ref = orc.partition(ref_plan, z_h)
-    t_part = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    out_ref = orc.reconstruct(ref_plan, preds_h)
-    t_rec = time.perf_counter() - t0
-    t_att = 0.0
-    flops = 0.0
-    max_err = mean_err = 0.0
+    t_part = t_rec = t_att = 0.0
+    flops = bytes_part = bytes_rec = 0.0
+    max_err = sum_err = 0.0
     n_cmp = 0
-    for kp, part in enumerate(ref_plan.parts):
-        n = part.n_tokens
-        if n == 0:
-            continue
-        q, k, v = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
-        rows = np.arange(0, n, stride, dtype=np.int64)
+    parity_latent = True
+    for dim in dims:
+        st, ref_plan = state[dim], plans[dim]
+        preds_h = st["preds"].cpu().numpy()
         t0 = time.perf_counter()
-        want = orc.attention(q, k, v, rows=rows)
-        t_att += time.perf_counter() - t0
-        flops += 4.0 * len(rows) * n * w.head_dim * w.heads
-        got_bits = st["qkv"][kp][4].cpu().numpy().view(np.uint16)
-        err = np.abs(synth.bf16_bits_to_f32(got_bits[rows]) - want)
-        max_err = max(max_err, float(err.max()))
-        mean_err += float(err.sum()); n_cmp += err.size
-    parity_latent = bool(np.array_equal(st["subs"].cpu().numpy(), subs_ref))
+        subs_ref = orc.partition(ref_plan, z_h)
+        t_part += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        orc.reconstruct(ref_plan, preds_h)
+        t_rec += time.perf_counter() - t0
+        bytes_part += 2 * 4.0 * ref_plan.total_elems
+        bytes_rec += 4.0 * (ref_plan.total_elems + int(np.prod(w.latent)))
+        parity_latent = parity_latent and bool(np.array_equal(st["subs"].cpu().numpy(), subs_ref))
+        for kp, part in enumerate(ref_plan.parts):
+            n = part.n_tokens
+            if n == 0:
+                continue
+            q, k, v = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
+            rows = np.arange(0, n, stride, dtype=np.int64)
+            t0 = time.perf_counter()
+            want = orc.attention(q, k, v, rows=rows)
+            t_att += time.perf_counter() - t0
+            flops += 4.0 * len(rows) * n * w.head_dim * w.heads
+            got_bits = st["qkv"][kp][4].cpu().numpy().view(np.uint16)
+            err = np.abs(synth.bf16_bits_to_f32(got_bits[rows]) - want)
+            max_err = max(max_err, float(err.max()))
+            sum_err += float(err.sum()); n_cmp += err.size
     return {"value": round(flops / t_att / 1e12, 5), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": "step along %s of %s: attention on every %d-th query row of all %d partitions (all keys, all heads; "
-                      "%.3g of %.3g flop) in %.1f s; partition %.1f ms and reconstruct %.1f ms in full"
-                      % (synth.DIM_NAMES[dim], w.name, stride, w.K, flops, total_flops, t_att, t_part * 1e3, t_rec * 1e3),
-            "partition_GBps": round(2 * 4.0 * ref_plan.total_elems / t_part / 1e9, 2),
-            "reconstruct_GBps": round(4.0 * (ref_plan.total_elems + int(np.prod(w.latent))) / t_rec / 1e9, 2),
-            "gpu_vs_oracle_on_sample": {"attention_max_abs": max_err, "attention_mean_abs": mean_err / max(n_cmp, 1),
+            "sample": "one step along each of %s of %s: attention on every %d-th query row of all %d partitions (all keys, "
+                      "all heads; %.3g of %.3g flop) in %.1f s; partition %.1f ms and reconstruct %.1f ms in full"
+                      % ("/".join(synth.DIM_NAMES[d] for d in dims), w.name, stride, w.K, flops, total_flops, t_att,
+                         t_part * 1e3, t_rec * 1e3),
+            "partition_GBps": round(bytes_part / t_part / 1e9, 2),
+            "reconstruct_GBps": round(bytes_rec / t_rec / 1e9, 2),
+            "gpu_vs_oracle_on_sample": {"attention_max_abs": max_err, "attention_mean_abs": sum_err / max(n_cmp, 1),
                                         "partition_bit_exact": parity_latent}}
 
 
