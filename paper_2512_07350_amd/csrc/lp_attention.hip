@@ -129,22 +129,33 @@ struct Lane {
     int t_end;                               // one past the segment's last tile
 };
 
+// One wave-wide global -> LDS load: lane L fetches the 16 bytes at byte offset voff + soff of
+// the buffer and they land at LDS address lds_addr + 16 L (lds_addr is wave-uniform and goes
+// through M0; bytes outside the buffer arrive as zeros).  Written as an assembly statement so
+// that the compiler keeps no record of it: told about such a load, it waits for ALL of them
+// (vmcnt(0)) before the next LDS read of any address, which would put the whole memory latency
+// of the tile just sent for in front of the operand reads of the tiles in use.  The waits that
+// order these loads against the reads of their own stage are wait_tile_loads + barrier.
+// Nothing else in this file uses M0.
+__device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
+}
+
 // global -> LDS loads of one K/V tile into the stage at byte offset stage_off.  One
-// wave-wide instruction moves 1024 bytes (lane L fills bytes 16L..16L+15 of the block).
-// Rows past token n-1 lie outside the buffers and arrive as zeros.
+// wave-wide instruction moves 1024 bytes.  Rows past token n-1 lie outside the buffers
+// and arrive as zeros.
 template <int D, int NB>
-__device__ __forceinline__ void issue_tile(unsigned char *smem, const Lane<D, NB> &c, int tile, uint32_t stage_off) {
+__device__ __forceinline__ void issue_tile(uint32_t lds0, const Lane<D, NB> &c, int tile, uint32_t stage_off) {
     using T = Tile<D, NB>;
     const uint32_t soff = uint32_t(tile) * c.tile_bytes;
 #pragma unroll
     for (int i = 0; i < Lane<D, NB>::kLd; ++i) {
-        // (operands go through plainly typed locals: the builtin is checked where it is written)
-        unsigned char *dst_k = smem + stage_off + c.ld_dst[i];
-        unsigned char *dst_v = dst_k + T::kTileBytes;
-        const uint32_t voff_k = c.k_voff[i], voff_v = c.v_voff[i];
-        const __amdgpu_buffer_rsrc_t rsrc_k = c.k_rsrc, rsrc_v = c.v_rsrc;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_k, LP_LDS_PTR(void, dst_k), 16, voff_k, soff, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_v, LP_LDS_PTR(void, dst_v), 16, voff_v, soff, 0, 0);
+        const uint32_t dst_k = __builtin_amdgcn_readfirstlane(lds0 + stage_off + c.ld_dst[i]);
+        load_to_lds_16(c.k_rsrc, dst_k, c.k_voff[i], soff);
+        load_to_lds_16(c.v_rsrc, dst_k + T::kTileBytes, c.v_voff[i], soff);
     }
 }
 
@@ -317,7 +328,7 @@ __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
 // from valid, if stale, LDS addresses.  MASK = false is for steps whose rounds i+1 lie
 // wholly inside the segment and keeps the step free of conditionals.
 template <int D, int NB, int SUB, bool MASK>
-__device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D, NB> &c, int i, bool first,
+__device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &c, int i, bool first,
                                               Pipe<D, NB> &w, f32x16 (&s_cur)[NB], f32x16 (&s_nxt)[NB],
                                               bf16x8 (&p_prev)[NB][2], bf16x8 (&p_cur)[NB][2]) {
     using T = Tile<D, NB>;
@@ -326,7 +337,7 @@ __device__ __forceinline__ void pipeline_step(unsigned char *smem, const Lane<D,
         if (!first) w.tile_off = next_stage<T::kStageBytes>(w.tile_off);
         wait_tile_loads<0>();              // tile t+1, issued one tile ago
         __syncthreads();
-        if (w.issue_t < c.t_end) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
+        if (w.issue_t < c.t_end) issue_tile<D, NB>(lds0, c, w.issue_t, w.issue_off);
         ++w.issue_t;
         w.issue_off = next_stage<T::kStageBytes>(w.issue_off);
         const uint32_t nxt_off = next_stage<T::kStageBytes>(w.tile_off);
@@ -455,7 +466,7 @@ __device__ __forceinline__ Segment next_segment(Walk &k, const AttnParams &a, ui
 // segment's tiles use the LDS stages in turn, from stage 0).  The caller has made sure
 // that no wave still reads the stages.
 template <int D, int NB>
-__device__ __forceinline__ void start_tiles(unsigned char *smem, const AttnParams &a, const Segment &seg,
+__device__ __forceinline__ void start_tiles(uint32_t lds0, const AttnParams &a, const Segment &seg,
                                             Lane<D, NB> &c, Pipe<D, NB> &w, int n, int64_t stride_tok) {
     using T = Tile<D, NB>;
     const int head = int(seg.unit) / a.n_qtiles;
@@ -474,7 +485,7 @@ __device__ __forceinline__ void start_tiles(unsigned char *smem, const AttnParam
     w.issue_t = seg.t_begin;
 #pragma unroll
     for (int t = 0; t < kStages - 2; ++t) {
-        if (w.issue_t < c.t_end) issue_tile<D, NB>(smem, c, w.issue_t, w.issue_off);
+        if (w.issue_t < c.t_end) issue_tile<D, NB>(lds0, c, w.issue_t, w.issue_off);
         w.issue_off += T::kStageBytes;
         ++w.issue_t;
     }
@@ -548,7 +559,7 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
     Segment seg = next_segment(walk, a, tpu, lp, gridDim.x);
     if (!seg.valid) return;
     Pipe<D, NB> w;
-    start_tiles<D, NB>(smem, a, seg, c, w, n, stride_tok);
+    start_tiles<D, NB>(lds0, a, seg, c, w, n, stride_tok);
     load_q<D, NB>(a, seg, w, n, stride_tok, wave, col, half);
 
     while (true) {
@@ -642,12 +653,12 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         // the last round (and a step past it, if the count is odd, adds nothing)
         int i = i_begin;
         for (; (i + 3) * 32 <= c.key_end; i += 2) {      // rounds i+1 and i+2 are whole
-            pipeline_step<D, NB, 0, false>(smem, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
-            pipeline_step<D, NB, 1, false>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+            pipeline_step<D, NB, 0, false>(lds0, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1, false>(lds0, c, i + 1, false, w, s_b, s_a, p_a, p_b);
         }
         for (; i <= i_end; i += 2) {
-            pipeline_step<D, NB, 0, true>(smem, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
-            pipeline_step<D, NB, 1, true>(smem, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+            pipeline_step<D, NB, 0, true>(lds0, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1, true>(lds0, c, i + 1, false, w, s_b, s_a, p_a, p_b);
         }
 
         // ---- the next segment's first tiles set out before this segment's results are
@@ -655,7 +666,7 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         const Segment nxt = next_segment(walk, a, tpu, lp, gridDim.x);
         if (nxt.valid) {
             __syncthreads();        // every wave has left this segment's tiles before their stages are refilled
-            start_tiles<D, NB>(smem, a, nxt, c, w, n, stride_tok);
+            start_tiles<D, NB>(lds0, a, nxt, c, w, n, stride_tok);
             load_q<D, NB>(a, nxt, w, n, stride_tok, wave, opaque(lane_id) % 32, opaque(lane_id) / 32);
         }
 
