@@ -2,13 +2,15 @@
 
     python -m paper_2512_07350_amd.profile_summary stats   <dir-or-csv>
     python -m paper_2512_07350_amd.profile_summary traffic <fetch-dir> <write-dir> --workload NAME [--json OUT]
+    python -m paper_2512_07350_amd.profile_summary counters <dir> [<dir> ...] [--kernel attention_kernel]
 
 `stats` reads `*_kernel_stats.csv` (from `rocprofv3 --kernel-trace --stats`) and prints one row
 per kernel of this library.  `traffic` reads the `*_counter_collection.csv` files of two
 `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; both counters are KiB per dispatch) of
 `bench.py --copy-calibration`, scales them by what the same counter reads for the plain device
 copy of known size, and prints bytes per launch; with --json it also writes the record
-`bench.py` reads for `roofline.traffic`.  Host-side text processing only: no GPU, no oracle.
+`bench.py` reads for `roofline.traffic`.  `counters` prints the mean per dispatch of every
+counter found for one kernel in any number of `--pmc` runs.  Host-side text processing only: no GPU, no oracle.
 """
 from __future__ import annotations
 
@@ -120,6 +122,20 @@ def traffic(fetch_dir: str, write_dir: str, workload: str, out_json: str | None,
             fh.write("\n")
 
 
+def counters(paths, kernel: str) -> None:
+    print("| counter | mean per dispatch | dispatches |")
+    print("|---|---|---|")
+    for path in paths:
+        acc = {}
+        for r in csv.DictReader(open(find_csv(path, "counter_collection.csv"))):
+            if kernel in r["Kernel_Name"]:
+                n, t = acc.get(r["Counter_Name"], (0, 0.0))
+                acc[r["Counter_Name"]] = (n + 1, t + float(r["Counter_Value"]))
+        for name in sorted(acc):
+            n, t = acc[name]
+            print("| %s | %.6g | %d |" % (name, t / n, n))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -129,9 +145,13 @@ def main() -> int:
     t.add_argument("--workload", required=True)
     t.add_argument("--json", default=None)
     t.add_argument("--algorithmic-bytes", type=float, default=None)
+    c = sub.add_parser("counters")
+    c.add_argument("paths", nargs="+"); c.add_argument("--kernel", default="attention_kernel")
     a = ap.parse_args()
     if a.cmd == "stats":
         stats(a.path)
+    elif a.cmd == "counters":
+        counters(a.paths, a.kernel)
     else:
         traffic(a.fetch_dir, a.write_dir, a.workload, a.json, a.algorithmic_bytes)
     return 0
