@@ -13,6 +13,8 @@
  *   lpo_weight         position-aware weight mask              (Sec. 3.4, Eq. 12)
  *   lpo_partition      sub-latent extraction                   (Sec. 3.3, Eq. 10)
  *   lpo_reconstruct    weighted averaging A/Z                  (Sec. 3.4, Eq. 13-17)
+ *   lpo_guided_step    per-partition classifier-free guidance, reconstruction and
+ *                      the sampler's update as one denoising step  (Sec. 3.2, Eq. 4-6)
  *   lpo_attention      global softmax self-attention inside one sub-latent
  *                      (supplement, proof of Theorem 1, step 3: attention acts
  *                      over all positions of the sub-latent) -- the textbook
@@ -196,6 +198,37 @@ void lpo_reconstruct(const int32_t latent[4], int32_t dim, int32_t K, const lpo_
                     }
                     out[lat_index(latent, c, t, h, w)] = A / Z;
                 }
+}
+
+/*
+ * One denoising step on the reconstructed prediction, in the paper's order:
+ *   Eq. 4  g_k = u_k + w (c_k - u_k)       on every element of every sub-latent prediction
+ *                                          (c = conditional, u = unconditional, w = guidance scale)
+ *   Eq. 5  pred = F({g_k}, d)              lpo_reconstruct
+ *   Eq. 6  z' = S(z, pred, t)              the sampler.  The paper leaves S open; taken here as
+ *                                          the affine update z' = a z + b pred with per-step
+ *                                          scalars a, b (an Euler step of a flow-matching
+ *                                          sampler is a = 1, b = sigma' - sigma).
+ * binary32 throughout, every operation rounded on its own: d = c - u, m = w d, g = u + m;
+ * then lpo_reconstruct's order; then p = a z, q = b pred, z' = p + q.
+ * `guided` is caller-provided scratch of the packed size.
+ */
+void lpo_guided_step(const int32_t latent[4], int32_t dim, int32_t K, const lpo_part *parts, int64_t total_elems,
+                     const float *cond, const float *uncond, float w, const float *z, float a, float b,
+                     float *guided, float *out)
+{
+    for (int64_t i = 0; i < total_elems; ++i) {
+        const float d = cond[i] - uncond[i];
+        const float m = w * d;
+        guided[i] = uncond[i] + m;
+    }
+    lpo_reconstruct(latent, dim, K, parts, guided, out);
+    const int64_t n = (int64_t)latent[0] * latent[1] * latent[2] * latent[3];
+    for (int64_t i = 0; i < n; ++i) {
+        const float p = a * z[i];
+        const float q = b * out[i];
+        out[i] = p + q;
+    }
 }
 
 static float bf16_to_f32(uint16_t b)

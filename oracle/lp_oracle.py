@@ -103,6 +103,9 @@ def _load():
         lib.lpo_partition.restype = None
         lib.lpo_reconstruct.argtypes = [i32p, C.c_int32, C.c_int32, C.POINTER(_Part), C.c_void_p, C.c_void_p]
         lib.lpo_reconstruct.restype = None
+        lib.lpo_guided_step.argtypes = [i32p, C.c_int32, C.c_int32, C.POINTER(_Part), C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_float, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
+        lib.lpo_guided_step.restype = None
         lib.lpo_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                       C.c_int32, C.c_int64, C.c_int64, C.c_double, C.c_void_p, C.c_int64]
         lib.lpo_attention.restype = C.c_int
@@ -161,6 +164,21 @@ def reconstruct(pl: Plan, preds: np.ndarray) -> np.ndarray:
     assert preds.shape == (pl.total_elems,)
     out = np.empty(pl.latent, dtype=np.float32)
     _load().lpo_reconstruct(_i32(pl.latent), pl.dim, pl.K, pl._c_parts(), preds.ctypes.data, out.ctypes.data)
+    return out
+
+
+def guided_step(pl: Plan, cond: np.ndarray, uncond: np.ndarray, guidance: float, z: np.ndarray,
+                coef_z: float, coef_pred: float) -> np.ndarray:
+    """Eq. 4-6: z' = coef_z * z + coef_pred * F({u_k + guidance (c_k - u_k)}), float32 [C,T,H,W]."""
+    cond = np.ascontiguousarray(cond, dtype=np.float32)
+    uncond = np.ascontiguousarray(uncond, dtype=np.float32)
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    assert cond.shape == uncond.shape == (pl.total_elems,) and z.shape == tuple(pl.latent)
+    scratch = np.empty(pl.total_elems, dtype=np.float32)
+    out = np.empty(pl.latent, dtype=np.float32)
+    _load().lpo_guided_step(_i32(pl.latent), pl.dim, pl.K, pl._c_parts(), pl.total_elems, cond.ctypes.data,
+                            uncond.ctypes.data, float(guidance), z.ctypes.data, float(coef_z), float(coef_pred),
+                            scratch.ctypes.data, out.ctypes.data)
     return out
 
 
