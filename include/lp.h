@@ -121,6 +121,27 @@ int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *
 int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, void *stream);
 
 /*
+ * Eq. 4-6 as one pass: the denoising step on the reconstructed guided prediction,
+ *   g_k = u_k + guidance * (c_k - u_k)          per element of every sub-latent (Eq. 4)
+ *   pred = A / Z of the g_k                      as lp_reconstruct (Eq. 5, 12-17)
+ *   out = coef_z * z + coef_pred * pred          the sampler's update (Eq. 6)
+ * The paper leaves the sampler S open; this is the affine form z' = a z + b pred with
+ * per-step scalars (an Euler step of a flow-matching sampler: a = 1, b = sigma' - sigma).
+ * cond_packed, uncond_packed: device, conditional and unconditional predictions, both packed
+ * like lp_partition's output, read only.  z: device, lp_plan_latent_elems floats.  out: device,
+ * lp_plan_latent_elems floats, fully overwritten; out may be z itself (update in place) but must
+ * not overlap cond_packed or uncond_packed.
+ * Arithmetic is binary32, every operation rounded on its own, in this order: d = c - u,
+ * m = guidance * d, g = u + m; lp_reconstruct's order on g; p = coef_z * z, q = coef_pred * pred,
+ * out = p + q.  Results are reproducible bit for bit.
+ * Reads (2 gamma + 1) S_z bytes and writes S_z, against (4 gamma + 4) S_z for guidance,
+ * reconstruction and update as three passes.
+ */
+int lp_reconstruct_guided_step(const lp_plan *plan, const float *cond_packed, const float *uncond_packed,
+                               float guidance, const float *z, float coef_z, float coef_pred, float *out,
+                               void *stream);
+
+/*
  * Self-attention inside one sub-latent: for every head h and token i,
  *   o[i,h,:] = sum_j softmax_j(scale * <q[i,h,:], k[j,h,:]>) v[j,h,:]
  * over all n_tokens tokens j of the sub-latent (no mask, not causal): inside a

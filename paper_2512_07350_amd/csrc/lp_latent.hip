@@ -3,6 +3,7 @@
 //
 //   lp_partition    Sec. 3.3, Eq. 10   sub-latent k = z[..., s_k:e_k, ...]
 //   lp_reconstruct  Sec. 3.4, Eq. 12-17   out = A / Z, weights by Eq. 12
+//   lp_reconstruct_guided_step  Sec. 3.2, Eq. 4-6 around it: guidance before, sampler update after
 //
 // Both kernels see the latent as [outer, extent, inner] (outer = channels and
 // the dims before the partition dim, inner = the dims after it) and move
@@ -111,11 +112,31 @@ struct ReconstructArgs {
     int32_t ovl;                        // O * p: overlap in latent units (LANE_K)
 };
 
+// What the guided step adds to the reconstruction (Eq. 4 before it, Eq. 6 after it).
+struct GuidedArgs {
+    const float *uncond;   // unconditional predictions, packed like the conditional ones
+    const float *z;        // current latent
+    float w;               // guidance scale
+    float a, b;            // z' = a z + b pred
+};
+
 // Eq. 12 at local position j; the cases in the order the paper gives them.
 __device__ __forceinline__ float ramp_weight(int32_t j, int32_t len, int32_t ds, int32_t de) {
     if (j < ds) return __fdiv_rn(float(j), float(ds));
     if (j < len - de) return 1.0f;
     return __fdiv_rn(float(len - j), float(de));
+}
+
+// Eq. 4 on one vector: u + w (c - u), difference, product and sum each rounded.
+template <int VEC>
+__device__ __forceinline__ typename VecT<VEC>::type guide(const typename VecT<VEC>::type c,
+                                                          const typename VecT<VEC>::type u, float w) {
+    typename VecT<VEC>::type r;
+    const float *cf = reinterpret_cast<const float *>(&c), *uf = reinterpret_cast<const float *>(&u);
+    float *rf = reinterpret_cast<float *>(&r);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) rf[e] = __fadd_rn(uf[e], __fmul_rn(w, __fsub_rn(cf[e], uf[e])));
+    return r;
 }
 
 // One partition's term of Eq. 15-16 for the vector at x0 (local position j0 in partition k).
@@ -149,10 +170,13 @@ __device__ __forceinline__ void blend_term(const typename VecT<VEC>::type p, int
 // held in LDS; the test against s_k and e_k still decides.  Otherwise a wave
 // shares one or two x and the loop over all k with scalar loads is cheaper.
 // Both visit the covering partitions in ascending k, so the sums are identical.
-template <int VEC, bool X_PER_ELEM, bool LANE_K>
-__global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__restrict__ preds,
-                                                               float *__restrict__ out,
-                                                               const ReconstructArgs a) {
+// GUIDED: the prediction of partition k is formed on the fly as u + w (c - u) from the
+// conditional (`preds`) and unconditional sets (Eq. 4), and the result is the sampler's
+// update a z + b pred (Eq. 6); every operation is rounded on its own, in that order.
+// `out` may be the same buffer as g.z (each element is read and then written by one thread).
+template <int VEC, bool X_PER_ELEM, bool LANE_K, bool GUIDED>
+__global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__restrict__ preds, float *out,
+                                                               const ReconstructArgs a, const GuidedArgs g) {
     using V = typename VecT<VEC>::type;
     __shared__ int32_t plan_s[LANE_K ? LP_MAX_PARTS : 1], plan_e[LANE_K ? LP_MAX_PARTS : 1],
         plan_len[LANE_K ? LP_MAX_PARTS : 1], plan_ds[LANE_K ? LP_MAX_PARTS : 1], plan_de[LANE_K ? LP_MAX_PARTS : 1];
@@ -187,6 +211,7 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__re
 #pragma unroll
     for (int c = 0; c < VEC; ++c) { A[c] = 0.0f; Z[c] = 0.0f; }
     const V *pv = reinterpret_cast<const V *>(preds);
+    const V *uv = reinterpret_cast<const V *>(g.uncond);
     if (LANE_K) {
         const int k_lo = x0 >= a.ovl ? int(fastdiv(uint32_t(x0 - a.ovl), a.core_div)) : 0;
         const int k_hi = min(a.K - 1, int(fastdiv(uint32_t(x0 + a.ovl), a.core_div)));
@@ -200,7 +225,8 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__re
                 idx = uint64_t(plan_off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) / VEC;
             else
                 idx = uint64_t(plan_off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) * a.inner_vec + r_in;
-            blend_term<VEC, X_PER_ELEM>(pv[idx], j0, len, plan_ds[k], plan_de[k], A, Z);
+            blend_term<VEC, X_PER_ELEM>(GUIDED ? guide<VEC>(pv[idx], uv[idx], g.w) : pv[idx], j0, len, plan_ds[k],
+                                        plan_de[k], A, Z);
         }
     } else {
         for (int k = 0; k < a.K; ++k) {
@@ -209,13 +235,20 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__re
             const int32_t j0 = x0 - s;
             const int32_t len = a.len[k];
             const uint64_t idx = uint64_t(a.off[k]) + (uint64_t(o) * uint32_t(len) + uint32_t(j0)) * a.inner_vec + r_in;
-            blend_term<VEC, false>(pv[idx], j0, len, a.delta_start[k], a.delta_end[k], A, Z);
+            blend_term<VEC, false>(GUIDED ? guide<VEC>(pv[idx], uv[idx], g.w) : pv[idx], j0, len, a.delta_start[k],
+                                   a.delta_end[k], A, Z);
         }
     }
     V res;
     float *rf = reinterpret_cast<float *>(&res);
 #pragma unroll
     for (int c = 0; c < VEC; ++c) rf[c] = (Z[c] == 1.0f) ? A[c] : __fdiv_rn(A[c], Z[c]);   // Eq. 17 (A/1 = A)
+    if (GUIDED) {
+        const V zv = reinterpret_cast<const V *>(g.z)[i];
+        const float *zf = reinterpret_cast<const float *>(&zv);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) rf[c] = __fadd_rn(__fmul_rn(g.a, zf[c]), __fmul_rn(g.b, rf[c]));   // Eq. 6
+    }
     reinterpret_cast<V *>(out)[i] = res;
 }
 
@@ -259,8 +292,8 @@ int launch_partition(const lp_plan *pl, const float *z, float *subs, hipStream_t
                              stream, z, subs, a);
 }
 
-template <int VEC>
-int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, hipStream_t stream) {
+template <int VEC, bool GUIDED>
+int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, const GuidedArgs g, hipStream_t stream) {
     ReconstructArgs a;
     a.K = pl->K;
     for (int k = 0; k < pl->K; ++k) {
@@ -283,10 +316,10 @@ int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, hipStr
     // a wave of 64 vectors sits on at least 64 / inner_vec different x
     const bool lane_k = x_per_elem || a.inner_vec < 16;
     dim3 grid((a.n_vec + kThreads - 1) / kThreads);
-    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true, true>)
-                     : lane_k   ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, true>)
-                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, false>);
-    return lp::launch_kernel(fn, grid, dim3(kThreads), 0, stream, preds, out, a);
+    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true, true, GUIDED>)
+                     : lane_k   ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, true, GUIDED>)
+                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, false, GUIDED>);
+    return lp::launch_kernel(fn, grid, dim3(kThreads), 0, stream, preds, out, a, g);
 }
 
 // The kernels index with 32-bit vector counts; 2^31 vectors is far beyond any latent.
@@ -315,10 +348,33 @@ int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, v
     if (!aligned_to(preds_packed, 4) || !aligned_to(out, 4)) return LP_ERR_INVALID_ARG;
     if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const GuidedArgs none{};
     switch (pick_vec(plan, preds_packed, out)) {
-        case 4: return launch_reconstruct<4>(plan, preds_packed, out, st);
-        case 2: return launch_reconstruct<2>(plan, preds_packed, out, st);
-        default: return launch_reconstruct<1>(plan, preds_packed, out, st);
+        case 4: return launch_reconstruct<4, false>(plan, preds_packed, out, none, st);
+        case 2: return launch_reconstruct<2, false>(plan, preds_packed, out, none, st);
+        default: return launch_reconstruct<1, false>(plan, preds_packed, out, none, st);
+    }
+}
+
+int lp_reconstruct_guided_step(const lp_plan *plan, const float *cond_packed, const float *uncond_packed, float guidance,
+                               const float *z, float coef_z, float coef_pred, float *out, void *stream) {
+    if (plan == nullptr || cond_packed == nullptr || uncond_packed == nullptr || z == nullptr || out == nullptr)
+        return LP_ERR_INVALID_ARG;
+    if (!aligned_to(cond_packed, 4) || !aligned_to(uncond_packed, 4) || !aligned_to(z, 4) || !aligned_to(out, 4))
+        return LP_ERR_INVALID_ARG;
+    if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    GuidedArgs g;
+    g.uncond = uncond_packed;
+    g.z = z;
+    g.w = guidance;
+    g.a = coef_z;
+    g.b = coef_pred;
+    const int v1 = pick_vec(plan, cond_packed, out), v2 = pick_vec(plan, uncond_packed, z);
+    switch (v1 < v2 ? v1 : v2) {
+        case 4: return launch_reconstruct<4, true>(plan, cond_packed, out, g, st);
+        case 2: return launch_reconstruct<2, true>(plan, cond_packed, out, g, st);
+        default: return launch_reconstruct<1, true>(plan, cond_packed, out, g, st);
     }
 }
 

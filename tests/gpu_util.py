@@ -33,6 +33,17 @@ def hip_reconstruct(plan, preds: np.ndarray, latent) -> np.ndarray:
     return out.cpu().numpy()
 
 
+def hip_guided_step(plan, cond: np.ndarray, uncond: np.ndarray, guidance, z: np.ndarray, coef_z, coef_pred,
+                    in_place: bool = False) -> np.ndarray:
+    cd = torch.from_numpy(np.ascontiguousarray(cond, dtype=np.float32)).cuda()
+    ud = torch.from_numpy(np.ascontiguousarray(uncond, dtype=np.float32)).cuda()
+    zd = torch.from_numpy(np.ascontiguousarray(z, dtype=np.float32)).cuda()
+    out = zd if in_place else torch.full(tuple(z.shape), float("nan"), dtype=torch.float32, device="cuda")
+    lp.lp_reconstruct_guided_step(plan, cd, ud, guidance, zd, coef_z, coef_pred, out, stream())
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
 def to_dev_bf16(bits: np.ndarray) -> torch.Tensor:
     """uint16 bf16 bit patterns -> device tensor of dtype bfloat16 with the same bits."""
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)

@@ -57,6 +57,60 @@ def test_reconstruct_bit_exact(latent, patch, K, O, dim):
     assert got.tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("latent,patch,K,O,dim", _flat(CASES))
+def test_guided_step_bit_exact(latent, patch, K, O, dim):
+    # Eq. 4-6 in one pass against the oracle's three stages; also updating z in place
+    from tests import gpu_util as g
+    ref_plan = orc.plan(latent, patch, K, dim, overlap_patches=O)
+    cond = synth.normal_f32(synth.seed_for(9, dim, K, tensor=6), (ref_plan.total_elems,))
+    uncond = synth.normal_f32(synth.seed_for(9, dim, K, tensor=7), (ref_plan.total_elems,))
+    z = synth.latent(synth.seed_for(9, dim, K, tensor=8), latent)
+    w, a, b = 5.0, 0.9921875, -0.03125 * 1.37
+    want = orc.guided_step(ref_plan, cond, uncond, w, z, a, b)
+    plan = g.make_plan(latent, patch, K, dim, overlap_patches=O)
+    got = g.hip_guided_step(plan, cond, uncond, w, z, a, b)
+    assert got.tobytes() == want.tobytes()
+    assert g.hip_guided_step(plan, cond, uncond, w, z, a, b, in_place=True).tobytes() == want.tobytes()
+
+
+def test_guided_step_special_values_and_ratio_overlap():
+    from tests import gpu_util as g
+    latent = (16, 13, 60, 104)
+    for dim in range(3):
+        ref_plan = orc.plan(latent, P122, 4, dim, r=1.5)
+        cond = synth.normal_f32(2234 + dim, (ref_plan.total_elems,))
+        uncond = synth.normal_f32(3234 + dim, (ref_plan.total_elems,))
+        z = synth.latent(4234 + dim, latent)
+        plan = g.make_plan(latent, P122, 4, dim, overlap_ratio=1.5)
+        for w, a, b in ((0.0, 0.0, 1.0), (1.0, 1.0, 1.0), (7.5, 1.0, -1.0 / 3.0)):
+            want = orc.guided_step(ref_plan, cond, uncond, w, z, a, b)
+            assert g.hip_guided_step(plan, cond, uncond, w, z, a, b).tobytes() == want.tobytes()
+        # w = 0, a = 0, b = 1 is plain reconstruction of the unconditional set
+        assert g.hip_guided_step(plan, cond, uncond, 0.0, z, 0.0, 1.0).tobytes() == g.hip_reconstruct(plan, uncond, latent).tobytes()
+
+
+def test_guided_step_misaligned_buffers():
+    # base pointers offset by one float: the kernels must fall back to narrower vectors
+    from tests import gpu_util as g
+    import torch
+    from paper_2512_07350_amd import binding as lp
+    latent = (16, 9, 60, 104)
+    ref_plan = orc.plan(latent, P122, 4, 1, overlap_patches=1)
+    n, nz = ref_plan.total_elems, int(np.prod(latent))
+    cond = synth.normal_f32(91, (n,)); uncond = synth.normal_f32(92, (n,)); z = synth.latent(93, latent)
+    want = orc.guided_step(ref_plan, cond, uncond, 4.0, z, 1.0, -0.125)
+    plan = g.make_plan(latent, P122, 4, 1, overlap_patches=1)
+    for offs in ((1, 0, 0, 0), (0, 1, 0, 0), (0, 0, 1, 0), (0, 0, 0, 1), (2, 2, 2, 2)):
+        bufs = []
+        for host, off in zip((cond, uncond, z.reshape(-1), np.full(nz, np.nan, np.float32)), offs):
+            t = torch.empty(host.size + 4, dtype=torch.float32, device="cuda")
+            t[off:off + host.size].copy_(torch.from_numpy(host))
+            bufs.append(t[off:off + host.size])
+        lp.lp_reconstruct_guided_step(plan, bufs[0], bufs[1], 4.0, bufs[2], 1.0, -0.125, bufs[3], g.stream())
+        torch.cuda.synchronize()
+        assert bufs[3].cpu().numpy().tobytes() == want.tobytes(), offs
+
+
 @pytest.mark.parametrize("r", [0.5, 1.0, 1.5])
 def test_reconstruct_bit_exact_with_ratio_overlap(r):
     # r = 1.0 and 1.5 give non-dyadic ramps (Delta = 16, 26 ...) and three-way overlaps
