@@ -194,7 +194,7 @@ def main() -> int:
 
 
 def latent_per_dim(lp, torch, state, w, z, stream, synth, total_bytes=2 << 30, reps=3):
-    """lp_partition and lp_reconstruct per partition dimension, each timed as a run of launches
+    """lp_partition, lp_reconstruct and lp_reconstruct_guided_step per partition dimension, each timed as a run of launches
     back to back between two HIP events.  "warm": every call on the same buffers (operands in L2 / Infinity Cache).  "cold": each
     call on its own copy of the buffers, the copies together (about total_bytes) several times the
     last-level cache, so that operands come from HBM."""
@@ -222,15 +222,20 @@ def latent_per_dim(lp, torch, state, w, z, stream, synth, total_bytes=2 << 30, r
         subs = [torch.empty_like(st["subs"]) for _ in range(copies)]
         preds = [st["preds"].clone() for _ in range(copies)]
         outs = [torch.empty_like(z) for _ in range(copies)]
+        # the guided step reads a second prediction set: the sub-latent buffers stand in for it
+        guided = lambda c0, c1: lp.lp_reconstruct_guided_step(plan, preds[c0], subs[c0], 5.0, zs[c1], 1.0, -0.02,
+                                                              outs[c1], stream)
         t = {"warm": {"partition": timed(lambda c: lp.lp_partition(plan, zs[0], subs[0], stream), 50),
-                      "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[0], outs[0], stream), 50)},
+                      "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[0], outs[0], stream), 50),
+                      "guided_step": timed(lambda c: guided(0, 0), 50)},
              "cold": {"partition": timed(lambda c: lp.lp_partition(plan, zs[c], subs[c], stream), copies),
-                      "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[c], outs[c], stream), copies)}}
-        nbytes = {"partition": 2.0 * s_ext, "reconstruct": float(s_ext + s_z)}
+                      "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[c], outs[c], stream), copies),
+                      "guided_step": timed(lambda c: guided(c, c), copies)}}
+        nbytes = {"partition": 2.0 * s_ext, "reconstruct": float(s_ext + s_z), "guided_step": 2.0 * s_ext + 2.0 * s_z}
         entry = {"gamma": round(s_ext / s_z, 4), "copies": copies}
         for cache in ("warm", "cold"):
             entry[cache] = {}
-            for name in ("partition", "reconstruct"):
+            for name in ("partition", "reconstruct", "guided_step"):
                 gbps = nbytes[name] / (t[cache][name] * 1e-3) / 1e9
                 entry[cache][name] = {"us": round(t[cache][name] * 1e3, 2), "GBps": round(gbps, 1),
                                       "frac": round(gbps / PEAK_HBM_GBPS, 4)}

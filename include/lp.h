@@ -175,6 +175,21 @@ int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n
                  float scale, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * lp_attention over `batch` independent items in one launch -- the conditional and the
+ * unconditional pass of a guided step (Eq. 4) are batch = 2.  Item b, token i, head h, element d
+ * lives at b * stride_batch + i * stride_tok + h * stride_head + d; items never attend to each
+ * other.  Everything else as lp_attention (batch = 1 is lp_attention).  Allowed layouts for
+ * batch > 1: the items one after the other (stride_batch at least the extent of one item), or,
+ * token-major, the items of a token side by side (stride_tok >= batch * stride_batch,
+ * stride_batch >= heads * stride_head); stride_batch a multiple of 8.  One launch deals all
+ * batch * heads * ceil(n_tokens / 256) query tiles over the compute units together, which for
+ * sequences of a few thousand tokens is measurably faster than one call per item.
+ */
+int lp_attention_batch(const void *q, const void *k, const void *v, void *o, int32_t batch, int64_t n_tokens,
+                       int32_t heads, int32_t head_dim, int64_t stride_batch, int64_t stride_tok,
+                       int64_t stride_head, float scale, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
  * Bytes of workspace lp_attention can use on the current device for this
  * head_dim (2 partial-result slots per compute unit; about 35 MB for head_dim
  * 128 on 256 compute units).  Negative LP_ERR_* on failure.

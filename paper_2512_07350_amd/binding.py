@@ -32,7 +32,7 @@ EXPORTS = (
     "lp_rotation_dim", "lp_plan_create", "lp_plan_destroy", "lp_plan_num_parts", "lp_plan_dim",
     "lp_plan_total_elems", "lp_plan_latent_elems", "lp_plan_query", "lp_partition", "lp_reconstruct",
     "lp_reconstruct_guided_step",
-    "lp_attention", "lp_attention_workspace_size", "lp_strerror", "lp_last_hip_error", "lp_version",
+    "lp_attention", "lp_attention_batch", "lp_attention_workspace_size", "lp_strerror", "lp_last_hip_error", "lp_version",
 )
 
 
@@ -98,6 +98,8 @@ def _lib():
         lib.lp_reconstruct_guided_step.restype = C.c_int
         lib.lp_attention.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i64, C.c_float, vp, i64, vp]
         lib.lp_attention.restype = C.c_int
+        lib.lp_attention_batch.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i64, i64, i64, C.c_float, vp, i64, vp]
+        lib.lp_attention_batch.restype = C.c_int
         lib.lp_attention_workspace_size.argtypes = [i32]
         lib.lp_attention_workspace_size.restype = i64
         lib.lp_strerror.argtypes = [C.c_int]
@@ -235,3 +237,11 @@ def lp_attention(q, k, v, o, n_tokens: int, heads: int, head_dim: int, stride_to
     _check(_lib().lp_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(o), int(n_tokens), int(heads), int(head_dim),
                                int(stride_tok), int(stride_head), float(scale), _ptr(workspace) or None,
                                int(workspace_bytes), stream or None), "lp_attention")
+
+
+def lp_attention_batch(q, k, v, o, batch: int, n_tokens: int, heads: int, head_dim: int, stride_batch: int,
+                       stride_tok: int, stride_head: int, scale: float = 0.0, workspace=None,
+                       workspace_bytes: int = 0, stream: Optional[int] = None) -> None:
+    _check(_lib().lp_attention_batch(_ptr(q), _ptr(k), _ptr(v), _ptr(o), int(batch), int(n_tokens), int(heads),
+                                     int(head_dim), int(stride_batch), int(stride_tok), int(stride_head), float(scale),
+                                     _ptr(workspace) or None, int(workspace_bytes), stream or None), "lp_attention_batch")

@@ -394,7 +394,8 @@ struct AttnParams {
     const __bf16 *q, *k, *v;
     __bf16 *o;
     float *ws;                 // slots for partial results: 2 per workgroup
-    int64_t stride_tok, stride_head;
+    int64_t stride_tok, stride_head, stride_batch;
+    int heads;                 // heads per batch item; a unit's head index counts batch * heads + head
     float scale_log2e;
     int n, n_qtiles, tiles_per_unit;
     int shared_units, whole_rounds;
@@ -408,6 +409,12 @@ struct AttnParams {
 // anyway; halving the rows halves the traffic of the merge).
 template <int D>
 constexpr int slot_floats() { return kBM * (D / 2 + 2); }
+
+// Element offset of the first token of head index bh = batch_item * heads + head.
+__device__ __forceinline__ int64_t head_offset(const AttnParams &a, int bh) {
+    const int b = bh / a.heads;
+    return int64_t(b) * a.stride_batch + int64_t(bh - b * a.heads) * a.stride_head;
+}
 
 // First iteration of (logical) workgroup p when W iterations are dealt to P workgroups.
 __device__ __forceinline__ uint32_t range_start(uint32_t p, uint32_t W, uint32_t P) {
@@ -469,8 +476,7 @@ template <int D, int NB>
 __device__ __forceinline__ void start_tiles(uint32_t lds0, const AttnParams &a, const Segment &seg,
                                             Lane<D, NB> &c, Pipe<D, NB> &w, int n, int64_t stride_tok) {
     using T = Tile<D, NB>;
-    const int head = int(seg.unit) / a.n_qtiles;
-    const int64_t head_off = int64_t(head) * a.stride_head;
+    const int64_t head_off = head_offset(a, int(seg.unit) / a.n_qtiles);
     c.key_end = min(n, seg.t_stop * kBN);
     c.t_end = seg.t_stop;
     {
@@ -497,7 +503,7 @@ __device__ __forceinline__ void load_q(const AttnParams &a, const Segment &seg, 
                                        int64_t stride_tok, int wave, int col, int half) {
     const int head = int(seg.unit) / a.n_qtiles;
     const int qtile = int(seg.unit) % a.n_qtiles;
-    const __bf16 *qh = a.q + int64_t(head) * a.stride_head;
+    const __bf16 *qh = a.q + head_offset(a, head);
     const int q0 = qtile * kBM + wave * (32 * NB);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -564,7 +570,7 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 
     while (true) {
         const int qtile = int(seg.unit) % a.n_qtiles;
-        const int64_t head_off = int64_t(int(seg.unit) / a.n_qtiles) * a.stride_head;
+        const int64_t head_off = head_offset(a, int(seg.unit) / a.n_qtiles);
         const int t_begin = seg.t_begin, t_stop = seg.t_stop;
         const int i_begin = 2 * t_begin;                 // rounds [i_begin, i_end) of 32 keys
         const int i_end = min(2 * t_stop, n_rounds);
@@ -743,7 +749,7 @@ __global__ __launch_bounds__(32 * (D / 16)) void combine_kernel(const AttnParams
     union { uint4 u[2]; bf16x2 p[8]; } ow;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ow.p[e] = to_bf16x2(acc[2 * e] * inv, acc[2 * e + 1] * inv);
-    uint4 *dst = reinterpret_cast<uint4 *>(a.o + int64_t(head) * a.stride_head + int64_t(qi) * a.stride_tok + ch * 16);
+    uint4 *dst = reinterpret_cast<uint4 *>(a.o + head_offset(a, head) + int64_t(qi) * a.stride_tok + ch * 16);
     dst[0] = ow.u[0];
     dst[1] = ow.u[1];
 }
@@ -837,10 +843,12 @@ extern "C" int64_t lp_attention_workspace_size(int32_t head_dim) {
     return head_dim == 128 ? workspace_bytes_for<128>(cus) : workspace_bytes_for<64>(cus);
 }
 
-extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
-                            int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
-                            float scale, void *workspace, int64_t workspace_bytes, void *stream) {
-    if (n_tokens < 0 || heads < 1) return LP_ERR_INVALID_ARG;
+namespace {
+
+int attention_call(const void *q, const void *k, const void *v, void *o, int32_t batch, int64_t n_tokens, int32_t heads,
+                   int32_t head_dim, int64_t stride_batch, int64_t stride_tok, int64_t stride_head, float scale,
+                   void *workspace, int64_t workspace_bytes, void *stream) {
+    if (n_tokens < 0 || heads < 1 || batch < 1) return LP_ERR_INVALID_ARG;
     if (head_dim != 64 && head_dim != 128) return LP_ERR_UNSUPPORTED;
     if (n_tokens == 0) return LP_OK;
     if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return LP_ERR_INVALID_ARG;
@@ -851,9 +859,19 @@ extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o
     const bool token_major = stride_tok >= int64_t(heads) * stride_head;
     const bool head_major = stride_head >= n_tokens * stride_tok && stride_tok >= head_dim;
     if (!token_major && !head_major) return LP_ERR_INVALID_ARG;
+    if (batch > 1) {
+        // items one after the other, or (token-major) the items of a token side by side
+        if (stride_batch < 0 || stride_batch % 8 != 0) return LP_ERR_INVALID_ARG;
+        const int64_t item = token_major ? n_tokens * stride_tok : int64_t(heads) * stride_head;
+        const bool outer = stride_batch >= item;
+        const bool inner = stride_tok >= int64_t(batch) * stride_batch && stride_batch >= int64_t(heads) * stride_head;
+        if (!outer && !inner) return LP_ERR_INVALID_ARG;
+    }
     // 32-bit addressing inside one head: byte offsets below 2^31, work items below 2^31
     if (n_tokens > (int64_t(1) << 24) || (n_tokens * stride_tok + head_dim) * 2 >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
-    const int64_t units = int64_t(heads) * ((n_tokens + kBM - 1) / kBM);
+    const int64_t all_heads = int64_t(batch) * heads;
+    if (all_heads >= (int64_t(1) << 24)) return LP_ERR_UNSUPPORTED;
+    const int64_t units = all_heads * ((n_tokens + kBM - 1) / kBM);
     if (units * ((n_tokens + kBN - 1) / kBN + kBoundaryTiles) >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
     if (!(scale > 0.0f)) scale = 1.0f / sqrtf(float(head_dim));
     AttnParams a{};
@@ -863,9 +881,28 @@ extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o
     a.o = static_cast<__bf16 *>(o);
     a.stride_tok = stride_tok;
     a.stride_head = stride_head;
+    a.stride_batch = batch > 1 ? stride_batch : 0;
+    a.heads = heads;
     a.scale_log2e = scale * 1.4426950408889634f;
     a.n = int(n_tokens);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (head_dim == 128) return launch<128, kBlocksPerWave>(a, heads, workspace, workspace_bytes, st);
-    return launch<64, kBlocksPerWave>(a, heads, workspace, workspace_bytes, st);
+    if (head_dim == 128) return launch<128, kBlocksPerWave>(a, int(all_heads), workspace, workspace_bytes, st);
+    return launch<64, kBlocksPerWave>(a, int(all_heads), workspace, workspace_bytes, st);
+}
+
+}  // namespace
+
+extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
+                            int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
+                            float scale, void *workspace, int64_t workspace_bytes, void *stream) {
+    return attention_call(q, k, v, o, 1, n_tokens, heads, head_dim, 0, stride_tok, stride_head, scale, workspace,
+                          workspace_bytes, stream);
+}
+
+extern "C" int lp_attention_batch(const void *q, const void *k, const void *v, void *o, int32_t batch, int64_t n_tokens,
+                                  int32_t heads, int32_t head_dim, int64_t stride_batch, int64_t stride_tok,
+                                  int64_t stride_head, float scale, void *workspace, int64_t workspace_bytes,
+                                  void *stream) {
+    return attention_call(q, k, v, o, batch, n_tokens, heads, head_dim, stride_batch, stride_tok, stride_head, scale,
+                          workspace, workspace_bytes, stream);
 }

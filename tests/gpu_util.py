@@ -80,6 +80,26 @@ def hip_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float = 0.
     return from_dev_bf16(od)
 
 
+def hip_attention_batch(items, scale: float = 0.0, balanced: bool = True, layout: str = "outer"):
+    """items: list of (q, k, v) uint16 [n, heads, d].  One lp_attention_batch call over all of
+    them; returns the list of float32 outputs.  layout "outer": [batch, n, heads, d];
+    "inner": [n, batch, heads, d] (the items of a token side by side)."""
+    b = len(items)
+    n, heads, d = items[0][0].shape
+    stack = lambda j: np.stack([it[j] for it in items], axis=0 if layout == "outer" else 1)
+    qd, kd, vd = to_dev_bf16(stack(0)), to_dev_bf16(stack(1)), to_dev_bf16(stack(2))
+    od = torch.full(tuple(qd.shape), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws, ws_bytes = workspace(d) if balanced else (None, 0)
+    if layout == "outer":
+        strides = (n * heads * d, heads * d, d)
+    else:
+        strides = (heads * d, b * heads * d, d)
+    lp.lp_attention_batch(qd, kd, vd, od, b, n, heads, d, strides[0], strides[1], strides[2], scale, ws, ws_bytes, stream())
+    torch.cuda.synchronize()
+    out = from_dev_bf16(od)
+    return [out[i] if layout == "outer" else out[:, i] for i in range(b)]
+
+
 # tolerance of the attention path against the fp32/fp64 oracle on N(0,1) inputs
 ATT_MAX_ABS = 2e-2
 ATT_MEAN_ABS = 2e-3

@@ -126,3 +126,8 @@ def test_device_calls_reject_bad_arguments_without_a_gpu():
     assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 64, 0.0, 8, 1 << 20, None) == lp.LP_ERR_INVALID_ARG   # workspace alignment
     assert lib.lp_attention(16, 16, 16, 16, 1 << 22, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED  # offsets past 2^31
     assert lib.lp_attention_workspace_size(96) == lp.LP_ERR_UNSUPPORTED
+    # batch: items must not overlap (outer: stride_batch >= one item; inner: fits between token and head strides)
+    assert lib.lp_attention_batch(16, 16, 16, 16, 0, 10, 4, 64, 0, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_batch(16, 16, 16, 16, 2, 10, 4, 64, 1280, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_batch(16, 16, 16, 16, 2, 10, 4, 64, 2564, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_batch(None, None, None, None, 2, 0, 4, 64, 2560, 256, 64, 0.0, None, 0, None) == lp.LP_OK

@@ -41,6 +41,34 @@ def test_work_split_across_workgroups(n, heads, hd):
     assert np.max(np.abs(split - plain)) <= 2e-2
 
 
+@pytest.mark.parametrize("layout", ["outer", "inner"])
+@pytest.mark.parametrize("balanced", [True, False], ids=["balanced", "tile-per-workgroup"])
+@pytest.mark.parametrize("n,heads,hd,batch", [(1000, 3, 128, 2), (333, 2, 64, 3), (64, 1, 128, 2), (1, 2, 64, 2)])
+def test_batch_items_are_independent_calls(n, heads, hd, batch, balanced, layout):
+    """lp_attention_batch (the conditional / unconditional pair of Eq. 4 is batch = 2): every item
+    against the oracle on that item alone."""
+    from tests import gpu_util as g
+    items = [synth.qkv_bf16(7000 + 10 * n + b, n, heads, hd) for b in range(batch)]
+    got = g.hip_attention_batch(items, balanced=balanced, layout=layout)
+    for b, (q, k, v) in enumerate(items):
+        g.assert_attention_close(got[b], orc.attention(q, k, v), "n=%d item %d %s" % (n, b, layout))
+
+
+def test_batch_pair_at_benchmark_size_sampled_rows():
+    # the 33-frame H partition of 4212 tokens, 12 x 128, as a conditional / unconditional pair
+    from tests import gpu_util as g
+    n, heads, hd = 4212, 12, 128
+    items = [synth.qkv_bf16(synth.seed_for(1, 1, 0, tensor=20 + b), n, heads, hd) for b in range(2)]
+    got = g.hip_attention_batch(items)
+    rows = synth.sample_rows(n, 96, seed=5, tile=256)
+    for b, (q, k, v) in enumerate(items):
+        g.assert_attention_close(got[b][rows], orc.attention(q, k, v, rows=rows), "pair item %d" % b)
+        assert np.all(np.isfinite(got[b]))
+    # and an item of the pair agrees with the same item computed alone
+    alone = g.hip_attention(*items[1])
+    assert np.max(np.abs(alone - got[1])) <= 2e-2
+
+
 def test_tiny_config_partitions_full_oracle():
     # tiny config: 2 partitions of 200 tokens, 4 heads x 64
     from tests import gpu_util as g
