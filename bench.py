@@ -37,6 +37,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--workload", type=int, default=1, help="index into the benchmark configurations (default 1)")
     ap.add_argument("--layers", type=int, default=0, help="attention calls per partition per step (0 = the workload's)")
+    ap.add_argument("--guided", action="store_true",
+                    help="time the guided step instead (Eq. 4-6): attention on the conditional / unconditional pair "
+                         "in one lp_attention_batch call per partition and layer, then lp_reconstruct_guided_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "attention_traffic.json"),
                     help="measured HBM bytes per attention launch (written from rocprofv3 --pmc runs; see profiles/)")
@@ -78,15 +81,23 @@ def main() -> int:
                 qkv.append(None)
                 continue
             host = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
+            if args.guided:   # second item of the pair: [2, n, heads, d]
+                other = synth.qkv_bf16(synth.seed_for(cfg, dim, kp, tensor=12), n, w.heads, w.head_dim)
+                host = [np.stack([a, b]) for a, b in zip(host, other)]
             dev = [torch.from_numpy(a.view(np.int16)).cuda() for a in host]
             qkv.append((n, dev[0], dev[1], dev[2], torch.empty_like(dev[0])))
-        state[dim] = dict(plan=plan, parts=parts, subs=subs, preds=preds, qkv=qkv)
+        preds_u = None
+        if args.guided:
+            preds_u = torch.from_numpy(synth.normal_f32(synth.seed_for(cfg, dim, 0, tensor=11), (plan.total_elems,))).cuda()
+        state[dim] = dict(plan=plan, parts=parts, subs=subs, preds=preds, preds_u=preds_u, qkv=qkv)
     ws_bytes = lp.lp_attention_workspace_size(w.head_dim)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
 
+    n_items = 2 if args.guided else 1
+
     def flops_of(n):
-        return 4.0 * n * n * w.head_dim * w.heads
+        return 4.0 * n * n * w.head_dim * w.heads * n_items
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -105,11 +116,18 @@ def main() -> int:
             n, qd, kd, vd, od = item
             for _ in range(layers):
                 a0 = ev(); a0.record()
-                lp.lp_attention(qd, kd, vd, od, n, w.heads, w.head_dim, w.heads * w.head_dim, w.head_dim, 0.0, ws, ws_bytes, stream)
+                if args.guided:
+                    lp.lp_attention_batch(qd, kd, vd, od, 2, n, w.heads, w.head_dim, n * w.heads * w.head_dim,
+                                          w.heads * w.head_dim, w.head_dim, 0.0, ws, ws_bytes, stream)
+                else:
+                    lp.lp_attention(qd, kd, vd, od, n, w.heads, w.head_dim, w.heads * w.head_dim, w.head_dim, 0.0, ws, ws_bytes, stream)
                 a1 = ev(); a1.record()
                 att.append((a0, a1, n))
         e2 = ev(); e2.record()
-        lp.lp_reconstruct(st["plan"], st["preds"], out, stream)
+        if args.guided:
+            lp.lp_reconstruct_guided_step(st["plan"], st["preds"], st["preds_u"], 5.0, z, 1.0, -0.02, out, stream)
+        else:
+            lp.lp_reconstruct(st["plan"], st["preds"], out, stream)
         e3 = ev(); e3.record()
         if rec is not None:
             rec.append((dim, e0, e1, att, e2, e3))
@@ -135,7 +153,8 @@ def main() -> int:
         s_ext = 4.0 * st["plan"].total_elems
         s_z = 4.0 * st["plan"].latent_elems
         part_bytes += 2.0 * s_ext              # read each selected element once, write it once
-        rec_bytes += s_ext + s_z               # read every prediction once, write the latent once
+        # read every prediction once (both sets and z when guided), write the latent once
+        rec_bytes += (2.0 * s_ext + 2.0 * s_z) if args.guided else (s_ext + s_z)
         d = per_dim.setdefault(synth.DIM_NAMES[dim], dict(ms=0.0, flops=0.0, launches=0))
         for a0, a1, n in att:
             t = a0.elapsed_time(a1)
@@ -159,7 +178,7 @@ def main() -> int:
     traffic = None
     if args.traffic_json and os.path.exists(args.traffic_json):
         rec = json.load(open(args.traffic_json))
-        if rec.get("workload") == w.name:
+        if rec.get("workload") == w.name and not args.guided:
             traffic = rec.get("attention_bytes_per_launch")
 
     result = {
@@ -169,7 +188,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "index": cfg, "latent": list(w.latent), "patch": list(w.patch), "K": w.K,
                    "overlap_patches": w.overlap_patches, "dims": [synth.DIM_NAMES[d] for d in w.dims],
-                   "heads": w.heads, "head_dim": w.head_dim, "attention_layers_per_partition": layers},
+                   "heads": w.heads, "head_dim": w.head_dim, "attention_layers_per_partition": layers,
+                   "guided_pair": bool(args.guided)},
         "roofline": {"kernel": "attention_kernel<%d>" % w.head_dim, "bound": "mfma",
                      "achieved": round(achieved, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
@@ -187,7 +207,7 @@ def main() -> int:
                                    "reconstruct": round(rec_ms / args.steps, 5)},
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.guided:
         result["cpu_baseline"] = cpu_baseline(w, cfg, state, synth, np, torch)
     print(json.dumps(result), flush=True)
     return 0
