@@ -70,7 +70,7 @@ def main() -> int:
     out = torch.empty_like(z)
     state = {}
     for dim in sorted(set(w.dims)):
-        plan = lp.lp_plan_create(w.latent, w.patch, w.K, dim, overlap_patches=w.overlap_patches)
+        plan = lp.lp_plan_create(w.latent, w.patch, w.K, dim, **w.overlap_args())
         parts = plan.parts()
         subs = torch.empty(plan.total_elems, dtype=torch.float32, device="cuda")
         preds = torch.from_numpy(synth.normal_f32(synth.seed_for(cfg, dim, 0, tensor=10), (plan.total_elems,))).cuda()
@@ -187,7 +187,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "index": cfg, "latent": list(w.latent), "patch": list(w.patch), "K": w.K,
-                   "overlap_patches": w.overlap_patches, "dims": [synth.DIM_NAMES[d] for d in w.dims],
+                   "overlap_patches": w.overlap_patches, "overlap_ratio": w.overlap_ratio, "dims": [synth.DIM_NAMES[d] for d in w.dims],
                    "heads": w.heads, "head_dim": w.head_dim, "attention_layers_per_partition": layers,
                    "guided_pair": bool(args.guided)},
         "roofline": {"kernel": "attention_kernel<%d>" % w.head_dim, "bound": "mfma",
@@ -271,7 +271,7 @@ def cpu_baseline(w, cfg, state, synth, np, torch):
     the GPU's attention output on those rows with the oracle's."""
     from oracle import lp_oracle as orc
     dims = sorted(state)
-    plans = {d: orc.plan(w.latent, w.patch, w.K, d, overlap_patches=w.overlap_patches) for d in dims}
+    plans = {d: orc.plan(w.latent, w.patch, w.K, d, **w.overlap_args()) for d in dims}
     total_flops = sum(4.0 * p.n_tokens ** 2 * w.head_dim * w.heads for d in dims for p in plans[d].parts)
     budget_flops = 2.5e12                     # 15-20 s of oracle work on 16 cores
     stride = max(1, int(np.ceil(total_flops / budget_flops)))

@@ -128,8 +128,11 @@ def rotation_dim(step_1based: int) -> int:
 
 
 def plan(latent: Sequence[int], patch: Sequence[int], K: int, dim: int, *,
-         overlap_patches: int = -1, r: float = 0.0) -> Plan:
-    """Eq. 7-9, 11: the K partitions of a [C,T,H,W] latent along ``dim``."""
+         overlap_patches: int = -1, r: float = 0.0, overlap_ratio: Optional[float] = None) -> Plan:
+    """Eq. 7-9, 11: the K partitions of a [C,T,H,W] latent along ``dim``.
+    ``overlap_ratio`` is another name for ``r``."""
+    if overlap_ratio is not None:
+        r = overlap_ratio
     if K < 1:
         raise ValueError("K must be >= 1")
     parts = (_Part * K)()

@@ -29,15 +29,25 @@ class Workload:
     heads: int
     head_dim: int
     layers: int = 1
+    overlap_ratio: Optional[float] = None  # r of Sec. 3.3 (O = floor(L r) per dim); overlap_patches is then -1
+
+    def overlap_args(self) -> dict:
+        """Keyword arguments of the plan constructors (library and oracle use the same names)."""
+        if self.overlap_ratio is not None:
+            return {"overlap_patches": -1, "overlap_ratio": float(self.overlap_ratio)}
+        return {"overlap_patches": self.overlap_patches}
 
 
-# The five benchmark configurations (index = position in the baseline's list).
+# The five benchmark configurations (index = position in the baseline's list), then the
+# setting of the paper's communication table: 49 frames at 480p, K = 4, overlap ratio 0.5 and 1.0.
 WORKLOADS = (
     Workload("tiny", (16, 5, 16, 16), (1, 2, 2), 2, 1, (2,), 4, 64),
     Workload("wan1.3b-33f-480p", (16, 9, 60, 104), (1, 2, 2), 4, 1, (0, 1, 2), 12, 128),
     Workload("wan1.3b-81f-480p", (16, 21, 60, 104), (1, 2, 2), 4, 2, (1,), 12, 128),
     Workload("dit14b-81f-720p", (16, 21, 90, 160), (1, 2, 2), 8, 2, (2,), 40, 128),
     Workload("wan1.3b-81f-480p-loop", (16, 21, 60, 104), (1, 2, 2), 4, 2, (0, 1, 2), 12, 128, layers=30),
+    Workload("wan1.3b-49f-480p-r0.5", (16, 13, 60, 104), (1, 2, 2), 4, -1, (0, 1, 2), 12, 128, overlap_ratio=0.5),
+    Workload("wan1.3b-49f-480p-r1.0", (16, 13, 60, 104), (1, 2, 2), 4, -1, (0, 1, 2), 12, 128, overlap_ratio=1.0),
 )
 
 
