@@ -27,9 +27,14 @@
 //    index swapped when K rows are read) so that the 8 probabilities a lane feeds
 //    to one MFMA belong to 8 consecutive keys; V^T operands then come from two
 //    ds_read_b64_tr_b16 (transposing LDS reads) of the row-major V tile.
-//  * K/V tiles go global -> LDS with global_load_lds_dwordx4 (kStages tiles
+//  * K/V tiles go global -> LDS with buffer_load_dwordx4 ... lds (kStages tiles
 //    resident), with XOR swizzles of the 16-byte granules chosen so that the K
 //    reads (ds_read_b128) and the V reads are free of bank conflicts.
+//  * One persistent workgroup per compute unit; the (query tile, key tile) space is
+//    dealt so that every workgroup gets the same cost, and a query tile shared by
+//    several workgroups is merged by combine_kernel (see AttnParams).
+//  * A segment's results leave as whole 128-byte lines through per-wave LDS
+//    staging, after the next segment's first tiles and Q rows have been sent for.
 #include <hip/hip_runtime.h>
 
 #include "lp_internal.h"
