@@ -194,3 +194,50 @@ def test_14b_shape_sampled_rows():
         rows = synth.sample_rows(n, 48, seed=kp, tile=256)
         g.assert_attention_close(got[rows], orc.attention(q, k, v, rows=rows), "14b k=%d n=%d" % (kp, n))
         assert np.all(np.isfinite(got))
+
+
+def test_random_shapes_and_layouts():
+    """Seeded random token counts, head counts, head dims, batch sizes and padded strides, in both
+    launch modes; every item against the oracle on all rows."""
+    from tests import gpu_util as g
+    import torch
+    from paper_2512_07350_amd import binding as lp
+    rng = np.random.default_rng(7350)
+    for case in range(24):
+        n = int(rng.choice([rng.integers(1, 70), rng.integers(70, 700), rng.integers(700, 2600)]))
+        heads = int(rng.integers(1, 6))
+        hd = int(rng.choice([64, 128]))
+        batch = int(rng.integers(1, 4))
+        balanced = bool(rng.integers(0, 2))
+        pad_h = 8 * int(rng.integers(0, 3))            # gap between heads of a token
+        pad_t = 8 * int(rng.integers(0, 3))            # gap between tokens
+        stride_head = hd + pad_h
+        stride_tok = heads * stride_head + pad_t
+        stride_batch = n * stride_tok + 8 * int(rng.integers(0, 5))
+        items = [synth.qkv_bf16(60000 + 10 * case + b, n, heads, hd) for b in range(batch)]
+        total = batch * stride_batch + 64
+
+        def pack(j):
+            buf = np.zeros(total, dtype=np.uint16)
+            for b, it in enumerate(items):
+                for h in range(heads):
+                    idx = (b * stride_batch + np.arange(n)[:, None] * stride_tok + h * stride_head + np.arange(hd)[None, :])
+                    buf[idx] = it[j][:, h, :]
+            return g.to_dev_bf16(buf)
+
+        qd, kd, vd = pack(0), pack(1), pack(2)
+        od = torch.full((total,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ws, ws_bytes = g.workspace(hd) if balanced else (None, 0)
+        lp.lp_attention_batch(qd, kd, vd, od, batch, n, heads, hd, stride_batch, stride_tok, stride_head, 0.0,
+                              ws, ws_bytes, g.stream())
+        torch.cuda.synchronize()
+        out = g.from_dev_bf16(od)
+        written = np.zeros(total, dtype=bool)
+        for b, (q, k, v) in enumerate(items):
+            want = orc.attention(q, k, v)
+            for h in range(heads):
+                idx = (b * stride_batch + np.arange(n)[:, None] * stride_tok + h * stride_head + np.arange(hd)[None, :])
+                written[idx] = True
+                g.assert_attention_close(out[idx], want[:, h, :], "case %d item %d head %d n=%d hd=%d" % (case, b, h, n, hd))
+        # nothing outside the rows of O was touched
+        assert np.all(np.isnan(out[~written])), "case %d wrote outside its rows" % case

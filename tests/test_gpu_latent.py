@@ -164,3 +164,33 @@ def test_misaligned_buffers_fall_back_to_narrower_vectors():
             out = obuf[shift:shift + n_lat].cpu().numpy().reshape(latent)
             assert out.tobytes() == orc.reconstruct(ref_plan, subs).tobytes()
             assert float(sbuf[:shift].abs().sum()) == 0.0 and float(obuf[shift + n_lat:].abs().sum()) == 0.0
+
+
+def test_random_shapes_bit_exact():
+    """Seeded random latents, patches, K, overlaps (count or ratio) and dims: partition,
+    reconstruction and the guided step against the oracle, bit for bit."""
+    from tests import gpu_util as g
+    rng = np.random.default_rng(20251207)
+    done = 0
+    while done < 40:
+        patch = tuple(int(rng.integers(1, 4)) for _ in range(3))
+        latent = (int(rng.integers(1, 6)),) + tuple(int(p * rng.integers(1, 13)) for p in patch)
+        dim = int(rng.integers(0, 3))
+        K = int(rng.integers(1, 9))
+        N = latent[1 + dim] // patch[dim]
+        L = -(-N // K)
+        if rng.random() < 0.5:
+            kw = {"overlap_patches": int(rng.integers(0, L * (K - 1) + 1))}
+        else:
+            kw = {"overlap_patches": -1, "overlap_ratio": float(rng.uniform(0.0, K - 1))}
+        ref_plan = orc.plan(latent, patch, K, dim, **kw)
+        plan = g.make_plan(latent, patch, K, dim, **kw)
+        assert plan.total_elems == ref_plan.total_elems, (latent, patch, K, dim, kw)
+        z = synth.latent(1000 + done, latent)
+        assert g.hip_partition(plan, z).tobytes() == orc.partition(ref_plan, z).tobytes(), (latent, patch, K, dim, kw)
+        cond = synth.normal_f32(2000 + done, (ref_plan.total_elems,))
+        uncond = synth.normal_f32(3000 + done, (ref_plan.total_elems,))
+        assert g.hip_reconstruct(plan, cond, latent).tobytes() == orc.reconstruct(ref_plan, cond).tobytes(), (latent, patch, K, dim, kw)
+        want = orc.guided_step(ref_plan, cond, uncond, 3.5, z, 0.875, 0.3)
+        assert g.hip_guided_step(plan, cond, uncond, 3.5, z, 0.875, 0.3).tobytes() == want.tobytes(), (latent, patch, K, dim, kw)
+        done += 1
