@@ -37,6 +37,8 @@
 //    staging, after the next segment's first tiles and Q rows have been sent for.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "lp_internal.h"
 
 namespace {
@@ -759,9 +761,9 @@ __global__ __launch_bounds__(32 * (D / 16)) void combine_kernel(const AttnParams
     dst[1] = ow.u[1];
 }
 
-// Compute units of the current device (queried once per device).
-int device_compute_units() {
-    static int cached_dev = -1, cached_cus = 0;
+// Compute units of the current device (each host thread remembers the last device it asked about).
+int device_compute_units(int *device = nullptr) {
+    static thread_local int cached_dev = -1, cached_cus = 0;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (dev != cached_dev) {
@@ -770,6 +772,7 @@ int device_compute_units() {
         cached_cus = cus;
         cached_dev = dev;
     }
+    if (device != nullptr) *device = dev;
     return cached_cus;
 }
 
@@ -778,15 +781,20 @@ int64_t workspace_bytes_for(int cus) { return int64_t(2) * cus * slot_floats<D>(
 
 template <int D, int NB>
 int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hipStream_t stream) {
-    static bool attr_set = false;   // per process; the attribute is per function
+    // The dynamic-LDS limit is an attribute of the function on a device: set once per device
+    // (a repeated set by a racing host thread is harmless).
+    static std::atomic<uint64_t> attr_set{0};
     const void *kern = reinterpret_cast<const void *>(&attention_kernel<D, NB>);
-    if (!attr_set) {
+    int dev = 0;
+    const int cus = device_compute_units(&dev);
+    const uint64_t dev_bit = dev < 64 ? (uint64_t(1) << dev) : 0;
+    if ((attr_set.load(std::memory_order_relaxed) & dev_bit) == 0) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, Tile<D, NB>::kBytes);
         if (e != hipSuccess) {
             lp::set_last_hip_error(int(e));
             return LP_ERR_HIP;
         }
-        attr_set = true;
+        attr_set.fetch_or(dev_bit, std::memory_order_relaxed);
     }
     a.n_qtiles = (a.n + kBM - 1) / kBM;
     a.tiles_per_unit = (a.n + kBN - 1) / kBN;
@@ -799,7 +807,6 @@ int launch(AttnParams a, int heads, void *workspace, int64_t workspace_bytes, hi
     a.shared_work = 0;
     a.unit_cost = tpu;
     a.shared_wgs = 0;
-    const int cus = device_compute_units();
     if (workspace != nullptr && cus > 0 && workspace_bytes >= workspace_bytes_for<D>(cus)) {
         // Candidate: one workgroup per compute unit takes floor(units / #CU) rounds of whole
         // units, and the units left over are shared evenly by as many workgroups as get at least
