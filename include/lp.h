@@ -13,6 +13,10 @@
  * This library is that per-device work for one GPU: the integer plan (host),
  * lp_partition, lp_attention and lp_reconstruct (device).  The K sub-latents
  * that LP places on K devices are processed in turn on the one device.
+ * With classifier-free guidance every sub-latent is denoised twice per step
+ * (Eq. 4); lp_attention_batch serves the pair in one launch and
+ * lp_reconstruct_guided_step folds guidance, reconstruction and the sampler's
+ * update (Eq. 4-6) into one pass.
  *
  * Conventions
  *  - Every call returns an int status: LP_OK (0) or a negative LP_ERR_* code;
