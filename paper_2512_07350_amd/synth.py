@@ -39,7 +39,8 @@ class Workload:
 
 
 # The five benchmark configurations (index = position in the baseline's list), then the
-# setting of the paper's communication table: 49 frames at 480p, K = 4, overlap ratio 0.5 and 1.0.
+# setting of the paper's communication table (49 frames at 480p, K = 4, overlap ratio 0.5 and 1.0)
+# and three variations of the 81-frame case.
 WORKLOADS = (
     Workload("tiny", (16, 5, 16, 16), (1, 2, 2), 2, 1, (2,), 4, 64),
     Workload("wan1.3b-33f-480p", (16, 9, 60, 104), (1, 2, 2), 4, 1, (0, 1, 2), 12, 128),
@@ -48,6 +49,10 @@ WORKLOADS = (
     Workload("wan1.3b-81f-480p-loop", (16, 21, 60, 104), (1, 2, 2), 4, 2, (0, 1, 2), 12, 128, layers=30),
     Workload("wan1.3b-49f-480p-r0.5", (16, 13, 60, 104), (1, 2, 2), 4, -1, (0, 1, 2), 12, 128, overlap_ratio=0.5),
     Workload("wan1.3b-49f-480p-r1.0", (16, 13, 60, 104), (1, 2, 2), 4, -1, (0, 1, 2), 12, 128, overlap_ratio=1.0),
+    # the paper's sweeps over the number of devices and its temporal-only ablation, at 81 frames
+    Workload("wan1.3b-81f-480p-K2", (16, 21, 60, 104), (1, 2, 2), 2, 2, (0, 1, 2), 12, 128),
+    Workload("wan1.3b-81f-480p-K8", (16, 21, 60, 104), (1, 2, 2), 8, 2, (0, 1, 2), 12, 128),
+    Workload("wan1.3b-81f-480p-temporal-only", (16, 21, 60, 104), (1, 2, 2), 4, 2, (0,), 12, 128),
 )
 
 
