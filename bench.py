@@ -33,8 +33,11 @@ METRIC = "lp_attention TFLOP/s (% bf16 MFMA peak); partition+stitch GB/s (% HBM)
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--spinup-ms", type=float, default=200.0,
+                    help="run untimed steps for this long before the warm-up steps: the GPU needs some tens of "
+                         "milliseconds of load to settle at its running clock")
     ap.add_argument("--workload", type=int, default=1, help="index into the benchmark configurations (default 1)")
     ap.add_argument("--layers", type=int, default=0, help="attention calls per partition per step (0 = the workload's)")
     ap.add_argument("--guided", action="store_true",
@@ -99,7 +102,7 @@ def main() -> int:
     def flops_of(n):
         return 4.0 * n * n * w.head_dim * w.heads * n_items
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
+    ev, event_kind = event_factory(torch, stream)
 
     def run_step(step_1based, rec=None):
         dim = w.dims[(step_1based - 1) % len(w.dims)]
@@ -134,6 +137,13 @@ def main() -> int:
         if rec is not None:
             rec.append((dim, e0, e1, att, e2, e3))
 
+    t_spin = time.perf_counter() + args.spinup_ms * 1e-3
+    spin_steps = 0
+    while time.perf_counter() < t_spin:
+        for i in range(len(w.dims)):
+            run_step(i + 1)
+        torch.cuda.synchronize()
+        spin_steps += len(w.dims)
     for i in range(args.warmup):
         run_step(i + 1)
     torch.cuda.synchronize()
@@ -185,7 +195,8 @@ def main() -> int:
 
     result = {
         "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "spinup_steps": spin_steps,
+        "events": event_kind, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "index": cfg, "latent": list(w.latent), "patch": list(w.patch), "K": w.K,
@@ -213,6 +224,63 @@ def main() -> int:
         result["cpu_baseline"] = cpu_baseline(w, cfg, state, synth, np, torch)
     print(json.dumps(result), flush=True)
     return 0
+
+
+def event_factory(torch, stream):
+    """Timing events for the marks between launches.  Preferred: HIP events created with
+    hipEventDisableSystemFence (for events that only measure time), recorded on `stream`; a
+    default event makes the device flush its caches at every mark, which costs the step a few
+    per cent.  Falls back to torch events if the HIP runtime cannot be bound."""
+    import ctypes as C
+
+    class TorchEvent:
+        def __init__(self):
+            self.e = torch.cuda.Event(enable_timing=True)
+
+        def record(self):
+            self.e.record()
+
+        def elapsed_time(self, other):
+            return self.e.elapsed_time(other.e)
+
+    try:
+        hip = C.CDLL("libamdhip64.so")       # the runtime torch has loaded
+        hip.hipEventCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+        hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        hip.hipEventDestroy.argtypes = [C.c_void_p]
+        k_disable_system_fence = 0x20000000
+
+        class HipEvent:
+            def __init__(self):
+                self.h = C.c_void_p()
+                if hip.hipEventCreateWithFlags(C.byref(self.h), k_disable_system_fence) != 0:
+                    raise RuntimeError("hipEventCreateWithFlags")
+
+            def record(self):
+                if hip.hipEventRecord(self.h, C.c_void_p(stream)) != 0:
+                    raise RuntimeError("hipEventRecord")
+
+            def elapsed_time(self, other):
+                ms = C.c_float()
+                if hip.hipEventElapsedTime(C.byref(ms), self.h, other.h) != 0:
+                    raise RuntimeError("hipEventElapsedTime")
+                return ms.value
+
+            def __del__(self):
+                if self.h:
+                    hip.hipEventDestroy(self.h)
+
+        a, b = HipEvent(), HipEvent()          # check the binding on a known piece of work
+        a.record()
+        torch.empty(1 << 20, device="cuda").zero_()
+        b.record()
+        torch.cuda.synchronize()
+        if not a.elapsed_time(b) > 0.0:
+            raise RuntimeError("no time between two events")
+        return HipEvent, "hip events without system fence"
+    except (OSError, AttributeError, RuntimeError):
+        return TorchEvent, "torch events"
 
 
 def latent_per_dim(lp, torch, state, w, z, stream, synth, total_bytes=2 << 30, reps=3):

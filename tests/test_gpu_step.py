@@ -56,3 +56,66 @@ def test_ratio_overlap_workloads_step(cfg):
     got = g.hip_attention(q, k, v)
     g.assert_attention_close(got[rows], orc.attention(q, k, v, rows=rows), "cfg %d n=%d" % (cfg, n))
     assert np.all(np.isfinite(got))
+
+
+def test_step_replays_from_a_captured_graph():
+    """The calls enqueue work only (no allocation, no synchronisation, no memset nodes), so a
+    whole step can be captured in a HIP graph after one eager warm-up.  Three replays with
+    the program's own eager work and synchronisations in between, each checked against the
+    eager result of the same inputs."""
+    import torch
+    from tests import gpu_util as g
+    from paper_2512_07350_amd import binding as lp
+    w = synth.WORKLOADS[0]
+    dim = w.dims[0]
+    plan = g.make_plan(w.latent, w.patch, w.K, dim, **w.overlap_args())
+    parts = plan.parts()
+    n, heads, hd = parts[0].n_tokens, w.heads, w.head_dim
+    zd = torch.from_numpy(synth.latent(1, w.latent)).cuda()
+    subs = torch.empty(plan.total_elems, dtype=torch.float32, device="cuda")
+    uncond = torch.from_numpy(synth.normal_f32(2, (plan.total_elems,))).cuda()
+    out = torch.empty_like(zd)
+    q, k, v = (g.to_dev_bf16(a) for a in synth.qkv_bf16(3, n, heads, hd))
+    o = torch.empty_like(q)
+    ws, ws_bytes = g.workspace(hd)
+    # a second, larger call whose query tiles are shared between workgroups (workspace + merge kernel)
+    n2, heads2, hd2 = 1000, 3, 128
+    q2, k2, v2 = (g.to_dev_bf16(a) for a in synth.qkv_bf16(4, n2, heads2, hd2))
+    o2 = torch.empty_like(q2)
+    ws2, ws2_bytes = g.workspace(hd2)
+
+    def step(stream):
+        lp.lp_partition(plan, zd, subs, stream)
+        lp.lp_attention(q, k, v, o, n, heads, hd, heads * hd, hd, 0.0, ws, ws_bytes, stream)
+        lp.lp_attention(q2, k2, v2, o2, n2, heads2, hd2, heads2 * hd2, hd2, 0.0, ws2, ws2_bytes, stream)
+        lp.lp_reconstruct_guided_step(plan, subs, uncond, 2.0, zd, 1.0, -0.25, out, stream)
+
+    step(g.stream())                      # eager warm-up: one-time function attributes are set here
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        zd.copy_(torch.from_numpy(synth.latent(10 + rep, w.latent)))
+        q.copy_(g.to_dev_bf16(synth.qkv_bf16(20 + rep, n, heads, hd)[0]))
+        k2.copy_(g.to_dev_bf16(synth.qkv_bf16(30 + rep, n2, heads2, hd2)[1]))
+        for t in (out, o, o2, subs):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_out, got_o, got_o2, got_subs = out.clone(), o.clone(), o2.clone(), subs.clone()
+        for t in (out, o, o2, subs):
+            t.fill_(float("nan"))
+        step(g.stream())
+        torch.cuda.synchronize()
+        assert torch.equal(got_subs, subs), rep
+        assert torch.equal(got_out, out), rep
+        assert torch.equal(got_o.view(torch.int16), o.view(torch.int16)), rep
+        assert torch.equal(got_o2.view(torch.int16), o2.view(torch.int16)), rep
+        assert not torch.isnan(o2.float()).any()
+    # and the last eager result is the oracle's
+    ref_plan = orc.plan(w.latent, w.patch, w.K, dim, **w.overlap_args())
+    z_h = zd.cpu().numpy()
+    want = orc.guided_step(ref_plan, orc.partition(ref_plan, z_h), uncond.cpu().numpy(), 2.0, z_h, 1.0, -0.25)
+    assert out.cpu().numpy().tobytes() == want.tobytes()
