@@ -42,7 +42,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="attention calls per partition per step (0 = the workload's)")
     ap.add_argument("--guided", action="store_true",
                     help="time the guided step instead (Eq. 4-6): attention on the conditional / unconditional pair "
-                         "in one lp_attention_batch call per partition and layer, then lp_reconstruct_guided_step")
+                         "in one lp_attention_batch call per partition and layer, then "
+                         "lp_reconstruct_guided_step_partition, which also writes the next step's sub-latents "
+                         "(so the step has no lp_partition launch of its own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "attention_traffic.json"),
                     help="measured HBM bytes per attention launch (written from rocprofv3 --pmc runs; see profiles/)")
@@ -111,7 +113,8 @@ def main() -> int:
         st = state[dim]
         # one event between consecutive launches: the end of one interval is the start of the next
         e0 = ev(); e0.record()
-        lp.lp_partition(st["plan"], z, st["subs"], stream)
+        if not args.guided:           # guided: the previous step's fused call has written these sub-latents
+            lp.lp_partition(st["plan"], z, st["subs"], stream)
         e1 = ev(); e1.record()
         att = []
         last = e1
@@ -130,12 +133,14 @@ def main() -> int:
                 last = a1
         e2 = last
         if args.guided:
-            lp.lp_reconstruct_guided_step(st["plan"], st["preds"], st["preds_u"], 5.0, z, 1.0, -0.02, out, stream)
+            nxt = state[w.dims[step_1based % len(w.dims)]]
+            lp.lp_reconstruct_guided_step_partition(st["plan"], st["preds"], st["preds_u"], 5.0, z, 1.0, -0.02, out,
+                                                    nxt["plan"], nxt["subs"], stream)
         else:
             lp.lp_reconstruct(st["plan"], st["preds"], out, stream)
         e3 = ev(); e3.record()
         if rec is not None:
-            rec.append((dim, e0, e1, att, e2, e3))
+            rec.append((dim, w.dims[step_1based % len(w.dims)], e0, e1, att, e2, e3))
 
     t_spin = time.perf_counter() + args.spinup_ms * 1e-3
     spin_steps = 0
@@ -158,15 +163,19 @@ def main() -> int:
     att_launches = 0
     part_ms = rec_ms = part_bytes = rec_bytes = 0.0
     per_dim = {}
-    for dim, e0, e1, att, e2, e3 in records:
+    for dim, next_dim, e0, e1, att, e2, e3 in records:
         st = state[dim]
         part_ms += e0.elapsed_time(e1)
         rec_ms += e2.elapsed_time(e3)
         s_ext = 4.0 * st["plan"].total_elems
         s_z = 4.0 * st["plan"].latent_elems
         part_bytes += 2.0 * s_ext              # read each selected element once, write it once
-        # read every prediction once (both sets and z when guided), write the latent once
-        rec_bytes += (2.0 * s_ext + 2.0 * s_z) if args.guided else (s_ext + s_z)
+        # read every prediction once, write the latent once; guided: both sets and z read, and the
+        # next step's sub-latents written as well
+        if args.guided:
+            rec_bytes += 2.0 * s_ext + 2.0 * s_z + 4.0 * state[next_dim]["plan"].total_elems
+        else:
+            rec_bytes += s_ext + s_z
         d = per_dim.setdefault(synth.DIM_NAMES[dim], dict(ms=0.0, flops=0.0, launches=0))
         for a0, a1, n in att:
             t = a0.elapsed_time(a1)
@@ -315,22 +324,32 @@ def latent_per_dim(lp, torch, state, w, z, stream, synth, total_bytes=2 << 30, r
         # the guided step reads a second prediction set: the sub-latent buffers stand in for it
         guided = lambda c0, c1: lp.lp_reconstruct_guided_step(plan, preds[c0], subs[c0], 5.0, zs[c1], 1.0, -0.02,
                                                               outs[c1], stream)
+        # fused with the partition for the following step (the next dim of the rotation); the
+        # second prediction set's buffer cannot double as the destination here
+        dims_sorted = sorted(state)
+        nxt_plan = state[w.dims[(w.dims.index(dim) + 1) % len(w.dims)]]["plan"]
+        nxt_subs = [torch.empty(nxt_plan.total_elems, dtype=torch.float32, device="cuda") for _ in range(copies)]
+        fused = lambda c0, c1: lp.lp_reconstruct_guided_step_partition(plan, preds[c0], subs[c0], 5.0, zs[c1], 1.0, -0.02,
+                                                                       outs[c1], nxt_plan, nxt_subs[c1], stream)
         t = {"warm": {"partition": timed(lambda c: lp.lp_partition(plan, zs[0], subs[0], stream), 50),
                       "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[0], outs[0], stream), 50),
-                      "guided_step": timed(lambda c: guided(0, 0), 50)},
+                      "guided_step": timed(lambda c: guided(0, 0), 50),
+                      "guided_step_partition": timed(lambda c: fused(0, 0), 50)},
              "cold": {"partition": timed(lambda c: lp.lp_partition(plan, zs[c], subs[c], stream), copies),
                       "reconstruct": timed(lambda c: lp.lp_reconstruct(plan, preds[c], outs[c], stream), copies),
-                      "guided_step": timed(lambda c: guided(c, c), copies)}}
-        nbytes = {"partition": 2.0 * s_ext, "reconstruct": float(s_ext + s_z), "guided_step": 2.0 * s_ext + 2.0 * s_z}
+                      "guided_step": timed(lambda c: guided(c, c), copies),
+                      "guided_step_partition": timed(lambda c: fused(c, c), copies)}}
+        nbytes = {"partition": 2.0 * s_ext, "reconstruct": float(s_ext + s_z), "guided_step": 2.0 * s_ext + 2.0 * s_z,
+                  "guided_step_partition": 2.0 * s_ext + 2.0 * s_z + 4.0 * nxt_plan.total_elems}
         entry = {"gamma": round(s_ext / s_z, 4), "copies": copies}
         for cache in ("warm", "cold"):
             entry[cache] = {}
-            for name in ("partition", "reconstruct", "guided_step"):
+            for name in ("partition", "reconstruct", "guided_step", "guided_step_partition"):
                 gbps = nbytes[name] / (t[cache][name] * 1e-3) / 1e9
                 entry[cache][name] = {"us": round(t[cache][name] * 1e3, 2), "GBps": round(gbps, 1),
                                       "frac": round(gbps / PEAK_HBM_GBPS, 4)}
         res[synth.DIM_NAMES[dim]] = entry
-        del zs, subs, preds, outs
+        del zs, subs, preds, outs, nxt_subs
     return res
 
 

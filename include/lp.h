@@ -146,6 +146,19 @@ int lp_reconstruct_guided_step(const lp_plan *plan, const float *cond_packed, co
                                void *stream);
 
 /*
+ * lp_reconstruct_guided_step followed by lp_partition of its result for the NEXT step (Eq. 4-6,
+ * then Eq. 10 along the next rotating dimension), in one pass: every element of the updated
+ * latent is written to `out` and to each sub-latent of next_plan that contains it, which saves
+ * the next step's partition launch and its read of the latent.  next_plan: a plan over the same
+ * latent extents (else LP_ERR_INVALID_ARG), normally along lp_rotation_dim(i + 1).
+ * next_subs_packed: device, lp_plan_total_elems(next_plan) floats, fully overwritten, must not
+ * overlap any other buffer.  Everything else, and every value written, as the two calls it replaces.
+ */
+int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_packed, const float *uncond_packed,
+                                         float guidance, const float *z, float coef_z, float coef_pred, float *out,
+                                         const lp_plan *next_plan, float *next_subs_packed, void *stream);
+
+/*
  * Self-attention inside one sub-latent: for every head h and token i,
  *   o[i,h,:] = sum_j softmax_j(scale * <q[i,h,:], k[j,h,:]>) v[j,h,:]
  * over all n_tokens tokens j of the sub-latent (no mask, not causal): inside a

@@ -31,7 +31,7 @@ LP_MAX_PARTS = 64
 EXPORTS = (
     "lp_rotation_dim", "lp_plan_create", "lp_plan_destroy", "lp_plan_num_parts", "lp_plan_dim",
     "lp_plan_total_elems", "lp_plan_latent_elems", "lp_plan_query", "lp_partition", "lp_reconstruct",
-    "lp_reconstruct_guided_step",
+    "lp_reconstruct_guided_step", "lp_reconstruct_guided_step_partition",
     "lp_attention", "lp_attention_batch", "lp_attention_workspace_size", "lp_strerror", "lp_last_hip_error", "lp_version",
 )
 
@@ -96,6 +96,8 @@ def _lib():
         lib.lp_reconstruct.restype = C.c_int
         lib.lp_reconstruct_guided_step.argtypes = [vp, vp, vp, C.c_float, vp, C.c_float, C.c_float, vp, vp]
         lib.lp_reconstruct_guided_step.restype = C.c_int
+        lib.lp_reconstruct_guided_step_partition.argtypes = [vp, vp, vp, C.c_float, vp, C.c_float, C.c_float, vp, vp, vp, vp]
+        lib.lp_reconstruct_guided_step_partition.restype = C.c_int
         lib.lp_attention.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i64, C.c_float, vp, i64, vp]
         lib.lp_attention.restype = C.c_int
         lib.lp_attention_batch.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i64, i64, i64, C.c_float, vp, i64, vp]
@@ -223,6 +225,15 @@ def lp_reconstruct_guided_step(plan: Plan, cond_packed, uncond_packed, guidance:
     _check(_lib().lp_reconstruct_guided_step(plan.handle, _ptr(cond_packed), _ptr(uncond_packed), float(guidance),
                                              _ptr(z), float(coef_z), float(coef_pred), _ptr(out), stream or None),
            "lp_reconstruct_guided_step")
+
+
+def lp_reconstruct_guided_step_partition(plan: Plan, cond_packed, uncond_packed, guidance: float, z, coef_z: float,
+                                         coef_pred: float, out, next_plan: Plan, next_subs_packed,
+                                         stream: Optional[int] = None) -> None:
+    _check(_lib().lp_reconstruct_guided_step_partition(plan.handle, _ptr(cond_packed), _ptr(uncond_packed),
+                                                       float(guidance), _ptr(z), float(coef_z), float(coef_pred),
+                                                       _ptr(out), next_plan.handle, _ptr(next_subs_packed),
+                                                       stream or None), "lp_reconstruct_guided_step_partition")
 
 
 def lp_attention_workspace_size(head_dim: int) -> int:

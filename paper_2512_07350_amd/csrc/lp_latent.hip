@@ -120,6 +120,21 @@ struct GuidedArgs {
     float a, b;            // z' = a z + b pred
 };
 
+// Where the updated latent goes besides `out`: the sub-latents of the NEXT step's partition
+// (Eq. 10 along the next rotating dimension), written in the same pass.
+struct ScatterArgs {
+    float *subs;                        // packed sub-latents of the next step; nullptr = none
+    int32_t s[LP_MAX_PARTS];            // Eq. 9 of the next step's plan
+    int32_t e[LP_MAX_PARTS];
+    int32_t len[LP_MAX_PARTS];
+    uint32_t off[LP_MAX_PARTS];         // first vector of sub-latent k
+    int32_t K;
+    uint32_t inner_vec;                 // inner / VEC, or 1 when the next partition dim is the vectorised one
+    int32_t x_per_elem;                 // the next partition dim is the vectorised one
+    FastDiv lat_run;                    // extent * inner of the next dim, in vectors
+    FastDiv inner_div;                  // inner of the next dim, in vectors
+};
+
 // Eq. 12 at local position j; the cases in the order the paper gives them.
 __device__ __forceinline__ float ramp_weight(int32_t j, int32_t len, int32_t ds, int32_t de) {
     if (j < ds) return __fdiv_rn(float(j), float(ds));
@@ -174,9 +189,13 @@ __device__ __forceinline__ void blend_term(const typename VecT<VEC>::type p, int
 // conditional (`preds`) and unconditional sets (Eq. 4), and the result is the sampler's
 // update a z + b pred (Eq. 6); every operation is rounded on its own, in that order.
 // `out` may be the same buffer as g.z (each element is read and then written by one thread).
-template <int VEC, bool X_PER_ELEM, bool LANE_K, bool GUIDED>
+// SCATTER: the updated latent is also written into every sub-latent of the next step's
+// partition that contains it (Eq. 10 along the next dimension), which saves that step's
+// lp_partition launch and its read of the latent.
+template <int VEC, bool X_PER_ELEM, bool LANE_K, bool GUIDED, bool SCATTER>
 __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__restrict__ preds, float *out,
-                                                               const ReconstructArgs a, const GuidedArgs g) {
+                                                               const ReconstructArgs a, const GuidedArgs g,
+                                                               const ScatterArgs sc) {
     using V = typename VecT<VEC>::type;
     __shared__ int32_t plan_s[LANE_K ? LP_MAX_PARTS : 1], plan_e[LANE_K ? LP_MAX_PARTS : 1],
         plan_len[LANE_K ? LP_MAX_PARTS : 1], plan_ds[LANE_K ? LP_MAX_PARTS : 1], plan_de[LANE_K ? LP_MAX_PARTS : 1];
@@ -250,6 +269,28 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__re
         for (int c = 0; c < VEC; ++c) rf[c] = __fadd_rn(__fmul_rn(g.a, zf[c]), __fmul_rn(g.b, rf[c]));   // Eq. 6
     }
     reinterpret_cast<V *>(out)[i] = res;
+    if (SCATTER) {
+        // this vector in the [outer, extent, inner] view around the next step's partition dim
+        const uint32_t o2 = fastdiv(i, sc.lat_run);
+        const uint32_t rem2 = i - o2 * sc.lat_run.d;
+        int32_t x2;
+        uint32_t r2;
+        if (sc.x_per_elem) {
+            x2 = int32_t(rem2) * VEC;
+            r2 = 0;
+        } else {
+            const uint32_t xq = fastdiv(rem2, sc.inner_div);
+            x2 = int32_t(xq);
+            r2 = rem2 - xq * sc.inner_div.d;
+        }
+        V *dst = reinterpret_cast<V *>(sc.subs);
+        for (int k = 0; k < sc.K; ++k) {
+            const int32_t s = sc.s[k];
+            if (x2 < s || x2 >= sc.e[k]) continue;      // (a vector never straddles s_k or e_k)
+            const uint64_t row = uint64_t(o2) * uint32_t(sc.len[k]) + uint32_t(x2 - s);
+            dst[sc.x_per_elem ? uint64_t(sc.off[k]) + row / VEC : uint64_t(sc.off[k]) + row * sc.inner_vec + r2] = res;
+        }
+    }
 }
 
 bool aligned_to(const void *p, int bytes) { return (reinterpret_cast<uintptr_t>(p) % bytes) == 0; }
@@ -292,8 +333,9 @@ int launch_partition(const lp_plan *pl, const float *z, float *subs, hipStream_t
                              stream, z, subs, a);
 }
 
-template <int VEC, bool GUIDED>
-int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, const GuidedArgs g, hipStream_t stream) {
+template <int VEC, bool GUIDED, bool SCATTER>
+int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, const GuidedArgs g, const lp_plan *next,
+                       float *next_subs, hipStream_t stream) {
     ReconstructArgs a;
     a.K = pl->K;
     for (int k = 0; k < pl->K; ++k) {
@@ -316,10 +358,26 @@ int launch_reconstruct(const lp_plan *pl, const float *preds, float *out, const 
     // a wave of 64 vectors sits on at least 64 / inner_vec different x
     const bool lane_k = x_per_elem || a.inner_vec < 16;
     dim3 grid((a.n_vec + kThreads - 1) / kThreads);
-    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true, true, GUIDED>)
-                     : lane_k   ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, true, GUIDED>)
-                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, false, GUIDED>);
-    return lp::launch_kernel(fn, grid, dim3(kThreads), 0, stream, preds, out, a, g);
+    ScatterArgs sc{};
+    if (SCATTER) {
+        sc.subs = next_subs;
+        sc.K = next->K;
+        for (int k = 0; k < next->K; ++k) {
+            const lp_part_info &q = next->part[k];
+            sc.s[k] = q.s;
+            sc.e[k] = q.e;
+            sc.len[k] = q.len;
+            sc.off[k] = uint32_t(q.elem_offset / VEC);
+        }
+        sc.x_per_elem = (next->inner % VEC) != 0;
+        sc.inner_vec = sc.x_per_elem ? 1 : uint32_t(next->inner / VEC);
+        sc.lat_run = make_fastdiv(uint32_t(int64_t(next->extent) * next->inner / VEC));
+        sc.inner_div = make_fastdiv(sc.inner_vec);
+    }
+    const void *fn = x_per_elem ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, true, true, GUIDED, SCATTER>)
+                     : lane_k   ? reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, true, GUIDED, SCATTER>)
+                                : reinterpret_cast<const void *>(&reconstruct_kernel<VEC, false, false, GUIDED, SCATTER>);
+    return lp::launch_kernel(fn, grid, dim3(kThreads), 0, stream, preds, out, a, g, sc);
 }
 
 // The kernels index with 32-bit vector counts; 2^31 vectors is far beyond any latent.
@@ -350,9 +408,9 @@ int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, v
     hipStream_t st = static_cast<hipStream_t>(stream);
     const GuidedArgs none{};
     switch (pick_vec(plan, preds_packed, out)) {
-        case 4: return launch_reconstruct<4, false>(plan, preds_packed, out, none, st);
-        case 2: return launch_reconstruct<2, false>(plan, preds_packed, out, none, st);
-        default: return launch_reconstruct<1, false>(plan, preds_packed, out, none, st);
+        case 4: return launch_reconstruct<4, false, false>(plan, preds_packed, out, none, nullptr, nullptr, st);
+        case 2: return launch_reconstruct<2, false, false>(plan, preds_packed, out, none, nullptr, nullptr, st);
+        default: return launch_reconstruct<1, false, false>(plan, preds_packed, out, none, nullptr, nullptr, st);
     }
 }
 
@@ -372,9 +430,39 @@ int lp_reconstruct_guided_step(const lp_plan *plan, const float *cond_packed, co
     g.b = coef_pred;
     const int v1 = pick_vec(plan, cond_packed, out), v2 = pick_vec(plan, uncond_packed, z);
     switch (v1 < v2 ? v1 : v2) {
-        case 4: return launch_reconstruct<4, true>(plan, cond_packed, out, g, st);
-        case 2: return launch_reconstruct<2, true>(plan, cond_packed, out, g, st);
-        default: return launch_reconstruct<1, true>(plan, cond_packed, out, g, st);
+        case 4: return launch_reconstruct<4, true, false>(plan, cond_packed, out, g, nullptr, nullptr, st);
+        case 2: return launch_reconstruct<2, true, false>(plan, cond_packed, out, g, nullptr, nullptr, st);
+        default: return launch_reconstruct<1, true, false>(plan, cond_packed, out, g, nullptr, nullptr, st);
+    }
+}
+
+int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_packed, const float *uncond_packed,
+                                         float guidance, const float *z, float coef_z, float coef_pred, float *out,
+                                         const lp_plan *next_plan, float *next_subs_packed, void *stream) {
+    if (plan == nullptr || cond_packed == nullptr || uncond_packed == nullptr || z == nullptr || out == nullptr ||
+        next_plan == nullptr || next_subs_packed == nullptr)
+        return LP_ERR_INVALID_ARG;
+    if (!aligned_to(cond_packed, 4) || !aligned_to(uncond_packed, 4) || !aligned_to(z, 4) || !aligned_to(out, 4) ||
+        !aligned_to(next_subs_packed, 4))
+        return LP_ERR_INVALID_ARG;
+    const lp_config &c0 = plan->cfg, &c1 = next_plan->cfg;
+    if (c0.C != c1.C || c0.T != c1.T || c0.H != c1.H || c0.W != c1.W) return LP_ERR_INVALID_ARG;   // one latent
+    if (!fits_32bit(plan) || !fits_32bit(next_plan)) return LP_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    GuidedArgs g;
+    g.uncond = uncond_packed;
+    g.z = z;
+    g.w = guidance;
+    g.a = coef_z;
+    g.b = coef_pred;
+    int vec = pick_vec(plan, cond_packed, out);
+    const int v2 = pick_vec(plan, uncond_packed, z), v3 = pick_vec(next_plan, next_subs_packed, out);
+    vec = v2 < vec ? v2 : vec;
+    vec = v3 < vec ? v3 : vec;
+    switch (vec) {
+        case 4: return launch_reconstruct<4, true, true>(plan, cond_packed, out, g, next_plan, next_subs_packed, st);
+        case 2: return launch_reconstruct<2, true, true>(plan, cond_packed, out, g, next_plan, next_subs_packed, st);
+        default: return launch_reconstruct<1, true, true>(plan, cond_packed, out, g, next_plan, next_subs_packed, st);
     }
 }
 

@@ -44,6 +44,18 @@ def hip_guided_step(plan, cond: np.ndarray, uncond: np.ndarray, guidance, z: np.
     return out.cpu().numpy()
 
 
+def hip_guided_step_partition(plan, cond, uncond, guidance, z, coef_z, coef_pred, next_plan, in_place=False):
+    """-> (updated latent, packed sub-latents of the next step), one fused launch."""
+    cd = torch.from_numpy(np.ascontiguousarray(cond, dtype=np.float32)).cuda()
+    ud = torch.from_numpy(np.ascontiguousarray(uncond, dtype=np.float32)).cuda()
+    zd = torch.from_numpy(np.ascontiguousarray(z, dtype=np.float32)).cuda()
+    out = zd if in_place else torch.full(tuple(z.shape), float("nan"), dtype=torch.float32, device="cuda")
+    subs = torch.full((max(next_plan.total_elems, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    lp.lp_reconstruct_guided_step_partition(plan, cd, ud, guidance, zd, coef_z, coef_pred, out, next_plan, subs, stream())
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), subs.cpu().numpy()[:next_plan.total_elems]
+
+
 def to_dev_bf16(bits: np.ndarray) -> torch.Tensor:
     """uint16 bf16 bit patterns -> device tensor of dtype bfloat16 with the same bits."""
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)

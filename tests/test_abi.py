@@ -118,6 +118,9 @@ def test_device_calls_reject_bad_arguments_without_a_gpu():
     assert lib.lp_reconstruct(None, 16, 16, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_reconstruct_guided_step(plan.handle, 16, None, 1.0, 16, 1.0, 1.0, 16, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_reconstruct_guided_step(plan.handle, 16, 16, 1.0, 18, 1.0, 1.0, 16, None) == lp.LP_ERR_INVALID_ARG   # z not float aligned
+    other = lp.lp_plan_create((16, 5, 16, 32), (1, 2, 2), 2, 1, overlap_patches=1)                                  # another latent
+    assert lib.lp_reconstruct_guided_step_partition(plan.handle, 16, 16, 1.0, 16, 1.0, 1.0, 16, other.handle, 16, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_reconstruct_guided_step_partition(plan.handle, 16, 16, 1.0, 16, 1.0, 1.0, 16, None, 16, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention(16, 16, 16, 16, 10, 4, 96, 384, 96, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED
     assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 60, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention(16, 16, 16, 8, 10, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG

@@ -73,6 +73,25 @@ def test_guided_step_bit_exact(latent, patch, K, O, dim):
     assert g.hip_guided_step(plan, cond, uncond, w, z, a, b, in_place=True).tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("latent,patch,K,O,dim", _flat(CASES))
+def test_guided_step_with_next_partition_bit_exact(latent, patch, K, O, dim):
+    # the fused call = the guided step, then Eq. 10 of its result along every possible next dim
+    from tests import gpu_util as g
+    ref_plan = orc.plan(latent, patch, K, dim, overlap_patches=O)
+    cond = synth.normal_f32(synth.seed_for(9, dim, K, tensor=6), (ref_plan.total_elems,))
+    uncond = synth.normal_f32(synth.seed_for(9, dim, K, tensor=7), (ref_plan.total_elems,))
+    z = synth.latent(synth.seed_for(9, dim, K, tensor=8), latent)
+    w, a, b = 5.0, 0.9921875, -0.03125 * 1.37
+    want_z = orc.guided_step(ref_plan, cond, uncond, w, z, a, b)
+    plan = g.make_plan(latent, patch, K, dim, overlap_patches=O)
+    for nxt in range(3):
+        next_ref = orc.plan(latent, patch, K, nxt, overlap_patches=O)
+        next_plan = g.make_plan(latent, patch, K, nxt, overlap_patches=O)
+        got_z, got_subs = g.hip_guided_step_partition(plan, cond, uncond, w, z, a, b, next_plan, in_place=(nxt == 1))
+        assert got_z.tobytes() == want_z.tobytes(), nxt
+        assert got_subs.tobytes() == orc.partition(next_ref, want_z).tobytes(), nxt
+
+
 def test_guided_step_special_values_and_ratio_overlap():
     from tests import gpu_util as g
     latent = (16, 13, 60, 104)
@@ -193,4 +212,11 @@ def test_random_shapes_bit_exact():
         assert g.hip_reconstruct(plan, cond, latent).tobytes() == orc.reconstruct(ref_plan, cond).tobytes(), (latent, patch, K, dim, kw)
         want = orc.guided_step(ref_plan, cond, uncond, 3.5, z, 0.875, 0.3)
         assert g.hip_guided_step(plan, cond, uncond, 3.5, z, 0.875, 0.3).tobytes() == want.tobytes(), (latent, patch, K, dim, kw)
+        # ... and fused with the partition of the result along another dim, with another K
+        nxt, K2 = int(rng.integers(0, 3)), int(rng.integers(1, 9))
+        next_ref = orc.plan(latent, patch, K2, nxt, overlap_patches=0)
+        next_plan = g.make_plan(latent, patch, K2, nxt, overlap_patches=0)
+        got_z, got_subs = g.hip_guided_step_partition(plan, cond, uncond, 3.5, z, 0.875, 0.3, next_plan)
+        assert got_z.tobytes() == want.tobytes(), (latent, patch, K, dim, kw, nxt, K2)
+        assert got_subs.tobytes() == orc.partition(next_ref, want).tobytes(), (latent, patch, K, dim, kw, nxt, K2)
         done += 1
