@@ -60,7 +60,7 @@ constexpr int kBlocksPerWave = 1;             // NB used by lp_attention
 constexpr int kBN = 64;                       // keys per LDS tile (two rounds of 32)
 constexpr int kStages = 4;                    // LDS stages: three tiles in use plus one arriving
 constexpr float kRescaleThreshold = 8.0f;     // log2 units the running max may lag behind
-constexpr uint32_t kBoundaryTiles = 3;        // what changing units costs a workgroup, in tile times
+constexpr uint32_t kBoundaryTiles = 4;        // what changing units costs a workgroup, in tile times
 
 template <int D, int NB>
 struct Tile {
