@@ -209,6 +209,7 @@ def test_random_shapes_and_layouts():
         hd = int(rng.choice([64, 128]))
         batch = int(rng.integers(1, 4))
         balanced = bool(rng.integers(0, 2))
+        scale = float(rng.choice([0.0, 0.03, 0.25]))   # 0 selects 1/sqrt(head_dim)
         pad_h = 8 * int(rng.integers(0, 3))            # gap between heads of a token
         pad_t = 8 * int(rng.integers(0, 3))            # gap between tokens
         stride_head = hd + pad_h
@@ -228,16 +229,39 @@ def test_random_shapes_and_layouts():
         qd, kd, vd = pack(0), pack(1), pack(2)
         od = torch.full((total,), float("nan"), dtype=torch.bfloat16, device="cuda")
         ws, ws_bytes = g.workspace(hd) if balanced else (None, 0)
-        lp.lp_attention_batch(qd, kd, vd, od, batch, n, heads, hd, stride_batch, stride_tok, stride_head, 0.0,
+        lp.lp_attention_batch(qd, kd, vd, od, batch, n, heads, hd, stride_batch, stride_tok, stride_head, scale,
                               ws, ws_bytes, g.stream())
         torch.cuda.synchronize()
         out = g.from_dev_bf16(od)
         written = np.zeros(total, dtype=bool)
         for b, (q, k, v) in enumerate(items):
-            want = orc.attention(q, k, v)
+            want = orc.attention(q, k, v, scale=scale if scale > 0 else None)
             for h in range(heads):
                 idx = (b * stride_batch + np.arange(n)[:, None] * stride_tok + h * stride_head + np.arange(hd)[None, :])
                 written[idx] = True
                 g.assert_attention_close(out[idx], want[:, h, :], "case %d item %d head %d n=%d hd=%d" % (case, b, h, n, hd))
         # nothing outside the rows of O was touched
         assert np.all(np.isnan(out[~written])), "case %d wrote outside its rows" % case
+
+
+@pytest.mark.parametrize("balanced", [True, False], ids=["balanced", "tile-per-workgroup"])
+def test_scores_that_keep_rising_along_the_keys(balanced):
+    """Keys ordered so that the scores grow by about two octaves from one 32-key round to the
+    next: the running maximum has to be raised (and the accumulated output rescaled) over and
+    over, across tiles and across the parts of a query tile that different workgroups compute."""
+    from tests import gpu_util as g
+    n, heads, hd = 1500, 2, 128
+    rng = np.random.default_rng(99)
+    base = rng.standard_normal((heads, hd)).astype(np.float32)
+    base /= np.linalg.norm(base, axis=1, keepdims=True)
+    qf = np.broadcast_to(base[None] * np.float32(np.sqrt(hd)) * 4.0, (n, heads, hd)) + 0.05 * rng.standard_normal((n, heads, hd)).astype(np.float32)
+    ramp = (np.arange(n, dtype=np.float32) / 32.0 * 0.35)[:, None, None]       # log-score slope per round, before scale
+    kf = base[None] * ramp + 0.05 * rng.standard_normal((n, heads, hd)).astype(np.float32)
+    vf = rng.standard_normal((n, heads, hd)).astype(np.float32)
+    q, k, v = (synth.f32_to_bf16_bits(a) for a in (qf, kf, vf))
+    got = g.hip_attention(q, k, v, balanced=balanced)
+    want = orc.attention(q, k, v)
+    g.assert_attention_close(got, want, "rising scores")
+    # and the same keys in reverse order (the first round already holds the maximum)
+    got_r = g.hip_attention(q, k[::-1].copy(), v[::-1].copy(), balanced=balanced)
+    g.assert_attention_close(got_r, want, "falling scores")
