@@ -277,8 +277,11 @@ def event_factory(torch, stream):
                 return ms.value
 
             def __del__(self):
-                if self.h:
-                    hip.hipEventDestroy(self.h)
+                try:
+                    if self.h:
+                        hip.hipEventDestroy(self.h)
+                except Exception:       # interpreter shutdown: the runtime may already be gone
+                    pass
 
         a, b = HipEvent(), HipEvent()          # check the binding on a known piece of work
         a.record()
