@@ -24,6 +24,8 @@
  *  - "device pointer" = memory the current HIP device can access (hipMalloc);
  *    "host pointer" = ordinary process memory.  Device pointers are borrowed
  *    until the work enqueued by the call has finished; the caller owns them.
+ *  - Where a call says that buffers must not alias or overlap, passing the very same address
+ *    for both is refused with LP_ERR_INVALID_ARG; partial overlaps are not detected.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Device work is enqueued on it and the call returns without waiting.  No
  *    call here synchronises, allocates or frees device memory.
@@ -117,7 +119,7 @@ int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *
  * Z = sum_k I_k(x) W^(k)_j, j = x - s_k, weights by Eq. 12 (front ramp
  * j/Delta_start, 1 on the core, rear ramp (l_k - j)/Delta_end).
  * preds_packed: device, same packing as lp_partition's output, read only.
- * out: device, lp_plan_latent_elems floats, fully overwritten.
+ * out: device, lp_plan_latent_elems floats, fully overwritten; must not alias preds_packed.
  * Arithmetic is binary32 in a fixed order -- k ascending from A = Z = 0,
  * w by one IEEE division, A += (w * pred) as a rounded product then a rounded
  * sum, out = A / Z by IEEE division -- so results are reproducible bit for bit.

@@ -865,6 +865,7 @@ int attention_call(const void *q, const void *k, const void *v, void *o, int32_t
     if (n_tokens == 0) return LP_OK;
     if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return LP_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return LP_ERR_INVALID_ARG;
+    if (o == q || o == k || o == v) return LP_ERR_INVALID_ARG;   // the output is written while inputs are still read
     if (workspace != nullptr && (!aligned16(workspace) || workspace_bytes < 0)) return LP_ERR_INVALID_ARG;
     if (stride_head < head_dim || stride_head % 8 != 0 || stride_tok % 8 != 0) return LP_ERR_INVALID_ARG;
     // rows of different (token, head) pairs must not overlap: either token-major or head-major

@@ -391,7 +391,7 @@ extern "C" {
 
 int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *stream) {
     if (plan == nullptr || z == nullptr || subs_packed == nullptr) return LP_ERR_INVALID_ARG;
-    if (!aligned_to(z, 4) || !aligned_to(subs_packed, 4)) return LP_ERR_INVALID_ARG;
+    if (!aligned_to(z, 4) || !aligned_to(subs_packed, 4) || z == subs_packed) return LP_ERR_INVALID_ARG;
     if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     switch (pick_vec(plan, z, subs_packed)) {
@@ -403,7 +403,7 @@ int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *
 
 int lp_reconstruct(const lp_plan *plan, const float *preds_packed, float *out, void *stream) {
     if (plan == nullptr || preds_packed == nullptr || out == nullptr) return LP_ERR_INVALID_ARG;
-    if (!aligned_to(preds_packed, 4) || !aligned_to(out, 4)) return LP_ERR_INVALID_ARG;
+    if (!aligned_to(preds_packed, 4) || !aligned_to(out, 4) || out == preds_packed) return LP_ERR_INVALID_ARG;
     if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const GuidedArgs none{};
@@ -420,6 +420,7 @@ int lp_reconstruct_guided_step(const lp_plan *plan, const float *cond_packed, co
         return LP_ERR_INVALID_ARG;
     if (!aligned_to(cond_packed, 4) || !aligned_to(uncond_packed, 4) || !aligned_to(z, 4) || !aligned_to(out, 4))
         return LP_ERR_INVALID_ARG;
+    if (out == cond_packed || out == uncond_packed) return LP_ERR_INVALID_ARG;   // only z may be updated in place
     if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     GuidedArgs g;
@@ -444,6 +445,9 @@ int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_
         return LP_ERR_INVALID_ARG;
     if (!aligned_to(cond_packed, 4) || !aligned_to(uncond_packed, 4) || !aligned_to(z, 4) || !aligned_to(out, 4) ||
         !aligned_to(next_subs_packed, 4))
+        return LP_ERR_INVALID_ARG;
+    if (out == cond_packed || out == uncond_packed || next_subs_packed == cond_packed ||
+        next_subs_packed == uncond_packed || next_subs_packed == z || next_subs_packed == out)
         return LP_ERR_INVALID_ARG;
     const lp_config &c0 = plan->cfg, &c1 = next_plan->cfg;
     if (c0.C != c1.C || c0.T != c1.T || c0.H != c1.H || c0.W != c1.W) return LP_ERR_INVALID_ARG;   // one latent

@@ -116,21 +116,26 @@ def test_device_calls_reject_bad_arguments_without_a_gpu():
     plan = lp.lp_plan_create((16, 5, 16, 16), (1, 2, 2), 2, 2, overlap_patches=1)
     assert lib.lp_partition(plan.handle, None, None, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_reconstruct(None, 16, 16, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_reconstruct_guided_step(plan.handle, 16, None, 1.0, 16, 1.0, 1.0, 16, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_reconstruct_guided_step(plan.handle, 16, 16, 1.0, 18, 1.0, 1.0, 16, None) == lp.LP_ERR_INVALID_ARG   # z not float aligned
+    assert lib.lp_reconstruct_guided_step(plan.handle, 16, None, 1.0, 48, 1.0, 1.0, 64, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_reconstruct_guided_step(plan.handle, 16, 32, 1.0, 50, 1.0, 1.0, 64, None) == lp.LP_ERR_INVALID_ARG   # z not float aligned
     other = lp.lp_plan_create((16, 5, 16, 32), (1, 2, 2), 2, 1, overlap_patches=1)                                  # another latent
-    assert lib.lp_reconstruct_guided_step_partition(plan.handle, 16, 16, 1.0, 16, 1.0, 1.0, 16, other.handle, 16, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_reconstruct_guided_step_partition(plan.handle, 16, 16, 1.0, 16, 1.0, 1.0, 16, None, 16, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 96, 384, 96, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED
-    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 60, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention(16, 16, 16, 8, 10, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_reconstruct_guided_step_partition(plan.handle, 16, 32, 1.0, 48, 1.0, 1.0, 64, other.handle, 80, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_reconstruct_guided_step_partition(plan.handle, 16, 32, 1.0, 48, 1.0, 1.0, 64, None, 80, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention(16, 32, 48, 64, 10, 4, 96, 384, 96, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED
+    assert lib.lp_attention(16, 32, 48, 64, 10, 4, 64, 256, 60, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention(16, 32, 48, 8, 10, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention(None, None, None, None, 0, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_OK
     assert lib.lp_attention(None, None, None, None, -1, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention(16, 16, 16, 16, 10, 4, 64, 256, 64, 0.0, 8, 1 << 20, None) == lp.LP_ERR_INVALID_ARG   # workspace alignment
-    assert lib.lp_attention(16, 16, 16, 16, 1 << 22, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED  # offsets past 2^31
+    assert lib.lp_attention(16, 32, 48, 64, 10, 4, 64, 256, 64, 0.0, 8, 1 << 20, None) == lp.LP_ERR_INVALID_ARG   # workspace alignment
+    assert lib.lp_attention(16, 32, 48, 64, 1 << 22, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_UNSUPPORTED  # offsets past 2^31
+    # a buffer passed as both input and output is refused (the same address; partial overlaps are the caller's business)
+    assert lib.lp_attention(16, 32, 48, 16, 10, 4, 64, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG   # o is q
+    assert lib.lp_partition(plan.handle, 16, 16, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_reconstruct(plan.handle, 16, 16, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_reconstruct_guided_step(plan.handle, 16, 32, 1.0, 48, 1.0, 1.0, 32, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention_workspace_size(96) == lp.LP_ERR_UNSUPPORTED
     # batch: items must not overlap (outer: stride_batch >= one item; inner: fits between token and head strides)
-    assert lib.lp_attention_batch(16, 16, 16, 16, 0, 10, 4, 64, 0, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention_batch(16, 16, 16, 16, 2, 10, 4, 64, 1280, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
-    assert lib.lp_attention_batch(16, 16, 16, 16, 2, 10, 4, 64, 2564, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_batch(16, 32, 48, 64, 0, 10, 4, 64, 0, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_batch(16, 32, 48, 64, 2, 10, 4, 64, 1280, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_batch(16, 32, 48, 64, 2, 10, 4, 64, 2564, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention_batch(None, None, None, None, 2, 0, 4, 64, 2560, 256, 64, 0.0, None, 0, None) == lp.LP_OK
