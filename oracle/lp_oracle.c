@@ -249,7 +249,8 @@ static float bf16_to_f32(uint16_t b)
  * all n keys.  out is [n_rows, heads, head_dim] binary32, dense.
  * The K and V rows of the current head are widened to binary64 once up front
  * (a change of storage, not of arithmetic).  Returns 0, or -1 if memory for
- * that copy or for the score rows cannot be had.
+ * that copy or for the per-thread score rows cannot be had (all of it is
+ * requested before the first parallel loop).
  */
 int lpo_attention(const uint16_t *q, const uint16_t *k, const uint16_t *v, float *out,
                   int64_t n, int32_t heads, int32_t head_dim,
@@ -259,10 +260,21 @@ int lpo_attention(const uint16_t *q, const uint16_t *k, const uint16_t *v, float
     if (rows == NULL) n_rows = n;
     if (n <= 0 || n_rows <= 0) return 0;
     const int64_t D = head_dim;
+    /* work buffers, one set per thread, all allocated before any parallel region */
+#ifdef _OPENMP
+    const int64_t nt = omp_get_max_threads();
+#else
+    const int64_t nt = 1;
+#endif
     double *kd = (double *)malloc((size_t)(n * D) * sizeof(double));
     double *vd = (double *)malloc((size_t)(n * D) * sizeof(double));
-    if (!kd || !vd) { free(kd); free(vd); return -1; }
-    int failed = 0;
+    double *score_all = (double *)malloc((size_t)(nt * n) * sizeof(double));
+    double *acc_all = (double *)malloc((size_t)(nt * D) * sizeof(double));
+    double *qrow_all = (double *)malloc((size_t)(nt * D) * sizeof(double));
+    if (!kd || !vd || !score_all || !acc_all || !qrow_all) {
+        free(kd); free(vd); free(score_all); free(acc_all); free(qrow_all);
+        return -1;
+    }
     for (int32_t h = 0; h < heads; ++h) {
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < n; ++j) {
@@ -273,53 +285,47 @@ int lpo_attention(const uint16_t *q, const uint16_t *k, const uint16_t *v, float
                 vd[j * D + d] = (double)bf16_to_f32(vj[d]);
             }
         }
-#pragma omp parallel
-        {
-            double *score = (double *)malloc((size_t)n * sizeof(double));
-            double *acc = (double *)malloc((size_t)D * sizeof(double));
-            double *qrow = (double *)malloc((size_t)D * sizeof(double));
-            if (!score || !acc || !qrow) {
-#pragma omp atomic write
-                failed = 1;
-            } else {
-#pragma omp for schedule(dynamic, 4)
-                for (int64_t ri = 0; ri < n_rows; ++ri) {
-                    const int64_t i = rows ? rows[ri] : ri;
-                    const uint16_t *qi = q + i * stride_tok + (int64_t)h * stride_head;
-                    for (int64_t d = 0; d < D; ++d) qrow[d] = (double)bf16_to_f32(qi[d]);
-                    /* pass 1: scores and their maximum */
-                    double mx = -INFINITY;
-                    for (int64_t j = 0; j < n; ++j) {
-                        const double *kj = kd + j * D;
-                        double dot = 0.0;
+#pragma omp parallel for schedule(dynamic, 4)
+        for (int64_t ri = 0; ri < n_rows; ++ri) {
+#ifdef _OPENMP
+            const int64_t me = omp_get_thread_num();
+#else
+            const int64_t me = 0;
+#endif
+            double *score = score_all + me * n, *acc = acc_all + me * D, *qrow = qrow_all + me * D;
+            const int64_t i = rows ? rows[ri] : ri;
+            const uint16_t *qi = q + i * stride_tok + (int64_t)h * stride_head;
+            for (int64_t d = 0; d < D; ++d) qrow[d] = (double)bf16_to_f32(qi[d]);
+            /* pass 1: scores and their maximum */
+            double mx = -INFINITY;
+            for (int64_t j = 0; j < n; ++j) {
+                const double *kj = kd + j * D;
+                double dot = 0.0;
 #pragma omp simd reduction(+ : dot)
-                        for (int64_t d = 0; d < D; ++d) dot += qrow[d] * kj[d];
-                        const double sj = scale * dot;
-                        score[j] = sj;
-                        if (sj > mx) mx = sj;
-                    }
-                    /* pass 2: exponentials and their sum */
-                    double denom = 0.0;
-                    for (int64_t j = 0; j < n; ++j) {
-                        score[j] = exp(score[j] - mx);
-                        denom += score[j];
-                    }
-                    /* pass 3: weighted sum of value rows */
-                    for (int64_t d = 0; d < D; ++d) acc[d] = 0.0;
-                    for (int64_t j = 0; j < n; ++j) {
-                        const double *vj = vd + j * D;
-                        const double pj = score[j] / denom;
-                        for (int64_t d = 0; d < D; ++d) acc[d] += pj * vj[d];
-                    }
-                    float *o = out + (ri * heads + h) * D;
-                    for (int64_t d = 0; d < D; ++d) o[d] = (float)acc[d];
-                }
+                for (int64_t d = 0; d < D; ++d) dot += qrow[d] * kj[d];
+                const double sj = scale * dot;
+                score[j] = sj;
+                if (sj > mx) mx = sj;
             }
-            free(score); free(acc); free(qrow);
+            /* pass 2: exponentials and their sum */
+            double denom = 0.0;
+            for (int64_t j = 0; j < n; ++j) {
+                score[j] = exp(score[j] - mx);
+                denom += score[j];
+            }
+            /* pass 3: weighted sum of value rows */
+            for (int64_t d = 0; d < D; ++d) acc[d] = 0.0;
+            for (int64_t j = 0; j < n; ++j) {
+                const double *vj = vd + j * D;
+                const double pj = score[j] / denom;
+                for (int64_t d = 0; d < D; ++d) acc[d] += pj * vj[d];
+            }
+            float *o = out + (ri * heads + h) * D;
+            for (int64_t d = 0; d < D; ++d) o[d] = (float)acc[d];
         }
     }
-    free(kd); free(vd);
-    return failed ? -1 : 0;
+    free(kd); free(vd); free(score_all); free(acc_all); free(qrow_all);
+    return 0;
 }
 
 /* Threads the parallel loops above run on (1 when built without OpenMP). */

@@ -54,6 +54,38 @@ def test_weights_last_core_past_the_end():
     assert _Z(pl, 9) == [1.0, 1.0, 1.0, 2.0, 1.0, 1.0, 2.0, 1.0, 1.0]
 
 
+def test_weights_and_blend_where_a_core_lies_wholly_past_the_end_by_hand():
+    # W = 40, p = 2, K = 8, O = 2: N = 20, L = ceil(20/8) = 3; cores [0,3) ... [18,21), [21,24).
+    # 8th partition (the paper's k = 8): alpha = 21 > N, alpha' = 19, beta' = min(20, 26) = 20, so it is
+    # the latent range [38, 40) with l = 2, and Eq. 11 as written gives
+    #   Delta_start = (21 - 19) * 2 = 4  (> l),   Delta_end = (20 - 24) * 2 = -8.
+    # Eq. 12, first case (j < Delta_start) holds for both positions: weights 0/4 and 1/4.
+    # (A Delta_start cut off at the end of the latent, (20 - 19) * 2 = 2, would give 0 and 1/2:
+    # this is where evaluating Eq. 11-12 as written and a clamped ramp length part ways.)
+    pl = orc.plan((1, 1, 2, 40), P122, 8, 2, overlap_patches=2)
+    p6, p7, p8 = pl.parts[5], pl.parts[6], pl.parts[7]
+    assert (p8.s, p8.e, p8.len, p8.delta_start, p8.delta_end) == (38, 40, 2, 4, -8)
+    assert _weights(p8) == [0.0, 0.25]
+    # 7th: core [18,21) runs past N: alpha' = 16, beta' = 20 -> [32, 40), Delta_start = 4, Delta_end = -2:
+    # front ramp 0, 1/4, 1/2, 3/4, then the second case up to j < 8 + 2, i.e. to the end
+    assert (p7.s, p7.e, p7.delta_start, p7.delta_end) == (32, 40, 4, -2)
+    assert _weights(p7) == [0.0, 0.25, 0.5, 0.75, 1.0, 1.0, 1.0, 1.0]
+    # 6th: core [15,18): alpha' = 13, beta' = 20 -> [26, 40), Delta = 4 on both sides
+    assert (p6.s, p6.e, p6.delta_start, p6.delta_end) == (26, 40, 4, 4)
+    assert _weights(p6) == [0.0, 0.25, 0.5, 0.75] + [1.0] * 6 + [1.0, 0.75, 0.5, 0.25]
+    # columns 36..39 are covered by partitions 6, 7 (and 8 from column 38): Z = W6 + W7 + W8
+    assert _Z(pl, 40)[36:40] == [2.0, 1.75, 1.5, 1.5]
+    # blend of three constants (1, 2, 4 for partitions 6, 7, 8; 0 elsewhere), columns 36..39:
+    #   (1*1 + 1*2)/2, (.75*1 + 1*2)/1.75, (.5*1 + 1*2 + 0*4)/1.5, (.25*1 + 1*2 + .25*4)/1.5
+    preds = np.zeros(pl.total_elems, dtype=np.float32)
+    for q, c in ((p6, 1.0), (p7, 2.0), (p8, 4.0)):
+        preds[q.elem_offset:q.elem_offset + q.n_elems] = c
+    out = orc.reconstruct(pl, preds)
+    f = np.float32
+    want = [f(3.0) / f(2.0), f(2.75) / f(1.75), f(2.5) / f(1.5), f(3.25) / f(1.5)]
+    assert out[0, 0, 0, 36:40].tolist() == want and out[0, 0, 1, 36:40].tolist() == want
+
+
 @pytest.mark.parametrize("K,O,dim", [(2, 1, 2), (4, 2, 1), (4, 1, 0), (3, 5, 1), (8, 2, 2), (5, 0, 1)])
 def test_weight_closed_form_and_normalisation(K, O, dim):
     latent = (2, 12, 36, 40)
