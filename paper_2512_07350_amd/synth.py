@@ -73,10 +73,14 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def normal_f32(seed: int, shape: Sequence[int]) -> np.ndarray:
-    """N(0,1) binary32 tensor from a fixed stream."""
-    rng = np.random.Generator(np.random.Philox(seed))
-    return rng.standard_normal(size=tuple(shape), dtype=np.float32)
+def normal_f32(seed: int, shape: Sequence[int], substream: int = 0) -> np.ndarray:
+    """N(0,1) binary32 tensor from a fixed stream.  `substream` selects one of the disjoint
+    stretches of that seed's Philox sequence (each 2^128 draws long), so tensors that share a
+    seed never share values, whatever other seeds are in use."""
+    bits = np.random.Philox(seed)
+    if substream:
+        bits = bits.jumped(substream)
+    return np.random.Generator(bits).standard_normal(size=tuple(shape), dtype=np.float32)
 
 
 def latent(seed: int, shape: Sequence[int]) -> np.ndarray:
@@ -93,17 +97,19 @@ def qkv_bf16(seed: int, n_tokens: int, heads: int, head_dim: int):
     """Q, K, V ~ N(0,1) rounded to bf16, each uint16 [n_tokens, heads, head_dim]."""
     out = []
     for t in range(3):
-        x = normal_f32(seed + 0x1000 * (t + 1), (n_tokens, heads, head_dim))
+        x = normal_f32(seed, (n_tokens, heads, head_dim), substream=t + 1)
         out.append(f32_to_bf16_bits(x))
     return tuple(out)
 
 
 def sample_rows(n: int, count: int, seed: int, tile: int = 64) -> np.ndarray:
-    """Query rows for sampled checks: first, last, rows on both sides of tile
-    edges near the start and the end, then seeded random rows; sorted, unique."""
+    """Query rows for sampled checks: first, last, the rows on both sides of every tile edge
+    among the first four and the last four tiles, then seeded random rows up to `count`;
+    sorted, unique."""
     picks = {0, n - 1}
-    for edge in (tile, 2 * tile, 4 * tile, (n // tile) * tile, ((n // tile) - 1) * tile,
-                 (n // (4 * tile)) * 4 * tile):
+    last_edge = (n // tile) * tile
+    edges = [m * tile for m in range(1, 5)] + [last_edge - m * tile for m in range(0, 4)]
+    for edge in edges:
         for r in (edge - 1, edge, edge + 1):
             if 0 <= r < n:
                 picks.add(r)

@@ -72,10 +72,12 @@ _workspaces = {}
 
 def workspace(head_dim: int):
     """(tensor, bytes): device scratch for lp_attention, allocated once per head_dim and
-    filled with NaN so that any read of a slot nobody wrote shows up in the result."""
+    refilled with NaN at every request, so that a read of a slot nobody wrote IN THIS CALL
+    shows up in the result (data left by an earlier call would look plausible)."""
     if head_dim not in _workspaces:
         nbytes = lp.lp_attention_workspace_size(head_dim)
-        _workspaces[head_dim] = (torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda"), nbytes)
+        _workspaces[head_dim] = (torch.empty((nbytes // 4,), dtype=torch.float32, device="cuda"), nbytes)
+    _workspaces[head_dim][0].fill_(float("nan"))
     return _workspaces[head_dim]
 
 
@@ -112,14 +114,21 @@ def hip_attention_batch(items, scale: float = 0.0, balanced: bool = True, layout
     return [out[i] if layout == "outer" else out[:, i] for i in range(b)]
 
 
-# tolerance of the attention path against the fp32/fp64 oracle on N(0,1) inputs
+# tolerance of the attention path against the fp32/fp64 oracle on N(0,1) inputs at the default
+# scale 1/sqrt(head_dim)
 ATT_MAX_ABS = 2e-2
 ATT_MEAN_ABS = 2e-3
 
 
-def assert_attention_close(got: np.ndarray, want: np.ndarray, what=""):
+def assert_attention_close(got: np.ndarray, want: np.ndarray, what="", sharpness: float = 1.0):
+    """sharpness = scale * sqrt(head_dim) when a test passes an explicit scale above the default:
+    the stated tolerance is for logits of unit variance; with logits `sharpness` times wider the
+    softmax concentrates on few keys (outputs no longer average down from |v| ~ 1 to ~ 1/sqrt(n))
+    and the rounding of the pre-scaled q to bf16 perturbs every logit `sharpness` times more, so
+    both bounds are widened by that factor (never narrowed)."""
+    f = max(1.0, float(sharpness))
     assert got.shape == want.shape
     assert np.all(np.isfinite(got)), what
     err = np.abs(got.astype(np.float64) - want.astype(np.float64))
-    assert err.max() <= ATT_MAX_ABS, (what, float(err.max()))
-    assert err.mean() <= ATT_MEAN_ABS, (what, float(err.mean()))
+    assert err.max() <= ATT_MAX_ABS * f, (what, float(err.max()))
+    assert err.mean() <= ATT_MEAN_ABS * f, (what, float(err.mean()))

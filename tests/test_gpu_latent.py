@@ -20,6 +20,9 @@ CASES = [
     ((5, 8, 12, 36), P122, 5, 3, (0, 1, 2)),             # overlap wider than the core: 3 partitions meet
     ((1, 2, 2, 2), P122, 1, 0, (0, 1, 2)),               # smallest latent, K = 1
     ((2, 3, 4, 6), P122, 7, 0, (0, 1, 2)),               # K > N: empty partitions
+    ((16, 21, 60, 104), P122, 2, 2, (0, 1, 2)),          # 81-frame 480p on 2 devices
+    ((16, 21, 60, 104), P122, 8, 2, (0, 1, 2)),          # ... on 8 (along T: last core past the end)
+    ((2, 3, 4, 40), P122, 8, 2, (2,)),                   # a core wholly past the end: front ramp longer than the partition
 ]
 
 

@@ -52,7 +52,7 @@ def test_ratio_overlap_workloads_step(cfg):
     kp = int(np.argmax([p.n_tokens for p in ref_plan.parts]))
     n = ref_plan.parts[kp].n_tokens
     q, k, v = synth.qkv_bf16(synth.seed_for(cfg, dim, kp), n, w.heads, w.head_dim)
-    rows = synth.sample_rows(n, 64, seed=cfg, tile=256)
+    rows = synth.sample_rows(n, 256, seed=cfg, tile=256)
     got = g.hip_attention(q, k, v)
     g.assert_attention_close(got[rows], orc.attention(q, k, v, rows=rows), "cfg %d n=%d" % (cfg, n))
     assert np.all(np.isfinite(got))
@@ -119,3 +119,41 @@ def test_step_replays_from_a_captured_graph():
     z_h = zd.cpu().numpy()
     want = orc.guided_step(ref_plan, orc.partition(ref_plan, z_h), uncond.cpu().numpy(), 2.0, z_h, 1.0, -0.25)
     assert out.cpu().numpy().tobytes() == want.tobytes()
+
+
+def test_chained_guided_steps_carry_the_latent():
+    """Seven denoising steps in a row, rotating T -> H -> W (Eq. 3), the way a sampling loop runs
+    them: step i's fused call updates the latent in place (Eq. 4-6) and writes the sub-latents
+    step i + 1 starts from (Eq. 10 along the next dimension); the latent and the packed
+    sub-latents never leave the device between steps.  Every intermediate latent and packed
+    buffer is compared bit for bit with the oracle's guided step -> partition chain."""
+    import torch
+    from tests import gpu_util as g
+    from paper_2512_07350_amd import binding as lp
+    latent, patch, K, O = (4, 6, 8, 12), (1, 2, 2), 3, 1
+    plans = [g.make_plan(latent, patch, K, d, overlap_patches=O) for d in range(3)]
+    refs = [orc.plan(latent, patch, K, d, overlap_patches=O) for d in range(3)]
+    z_ref = synth.latent(4242, latent)
+    zd = torch.from_numpy(z_ref.copy()).cuda()
+    dim = lp.lp_rotation_dim(1)
+    subs_d = torch.full((plans[dim].total_elems,), float("nan"), dtype=torch.float32, device="cuda")
+    lp.lp_partition(plans[dim], zd, subs_d, g.stream())
+    subs_ref = orc.partition(refs[dim], z_ref)
+    for i in range(1, 8):
+        dim, nxt = lp.lp_rotation_dim(i), lp.lp_rotation_dim(i + 1)
+        assert dim == orc.rotation_dim(i) and nxt == (dim + 1) % 3
+        torch.cuda.synchronize()
+        assert subs_d.cpu().numpy().tobytes() == subs_ref.tobytes(), "sub-latents entering step %d" % i
+        # stand-in predictions: the step's sub-latents plus seeded noise (both sides get the same arrays)
+        cond = subs_ref + np.float32(0.1) * synth.normal_f32(5000 + i, subs_ref.shape)
+        uncond = subs_ref + np.float32(0.1) * synth.normal_f32(6000 + i, subs_ref.shape)
+        w, a, b = 3.5, 1.0, np.float32(-0.05 - 0.01 * i).item()
+        next_d = torch.full((plans[nxt].total_elems,), float("nan"), dtype=torch.float32, device="cuda")
+        lp.lp_reconstruct_guided_step_partition(plans[dim], torch.from_numpy(cond).cuda(), torch.from_numpy(uncond).cuda(),
+                                                w, zd, a, b, zd, plans[nxt], next_d, g.stream())
+        z_ref = orc.guided_step(refs[dim], cond, uncond, w, z_ref, a, b)
+        subs_ref = orc.partition(refs[nxt], z_ref)
+        subs_d = next_d
+        torch.cuda.synchronize()
+        assert zd.cpu().numpy().tobytes() == z_ref.tobytes(), "latent after step %d" % i
+    assert subs_d.cpu().numpy().tobytes() == subs_ref.tobytes()
