@@ -8,8 +8,9 @@
 per kernel of this library.  `traffic` reads the `*_counter_collection.csv` files of two
 `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; both counters are KiB per dispatch) of
 `bench.py --copy-calibration`, scales them by what the same counter reads for the plain device
-copy of known size, and prints bytes per launch; with --json it also writes the record
-`bench.py` reads for `roofline.traffic`.  `counters` prints the mean per dispatch of every
+copy of known size, and prints bytes per launch; with --json it also writes (or replaces) this
+workload's record in the file `bench.py` reads for `roofline.traffic`; the record carries the
+SHA-256 of the attention source in this tree, so summarise before changing that file.  `counters` prints the mean per dispatch of every
 counter found for one kernel in any number of `--pmc` runs.  Host-side text processing only: no GPU, no oracle.
 """
 from __future__ import annotations
@@ -111,15 +112,29 @@ def traffic(fetch_dir: str, write_dir: str, workload: str, out_json: str | None,
             per_call += (c["fetch_bytes"] + c["write_bytes"]) * c["launches"] / a["launches"]
         print("per lp_attention call (attention kernel + its share of merge kernels): %.1f MB" % (per_call / 1e6))
     if out_json:
-        doc = {"workload": workload,
-               "command": "rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --kernel-trace -- python3 bench.py --steps 3 --warmup 1 "
-                          "--no-cpu-baseline --copy-calibration",
-               "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4), "kernels": rec,
-               "attention_bytes_per_launch": int(per_call) if per_call else None,
-               "algorithmic_bytes_per_launch": algorithmic}
+        # one record per workload; a record names the attention source it was measured with, so that
+        # a reader (bench.py) can tell a stale record from a current one
+        rec_doc = {"workload": workload, "attention_source_sha256": source_sha256(),
+                   "command": "rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --kernel-trace -- python3 bench.py --workload <index> --only "
+                              "--steps 3 --warmup 1 --no-cpu-baseline --copy-calibration",
+                   "fetch_scale": round(f_scale, 4), "write_scale": round(w_scale, 4), "kernels": rec,
+                   "attention_bytes_per_launch": int(per_call) if per_call else None,
+                   "algorithmic_bytes_per_launch": algorithmic}
+        doc = {"records": []}
+        if os.path.exists(out_json):
+            old = json.load(open(out_json))
+            doc["records"] = [r for r in old.get("records", []) if r.get("workload") != workload]
+        doc["records"].append(rec_doc)
         with open(out_json, "w") as fh:
             json.dump(doc, fh, indent=1)
             fh.write("\n")
+
+
+def source_sha256() -> str:
+    """SHA-256 of the attention kernel's source file as it is in this tree."""
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    return hashlib.sha256(open(os.path.join(here, "csrc", "lp_attention.hip"), "rb").read()).hexdigest()
 
 
 def counters(paths, kernel: str) -> None:

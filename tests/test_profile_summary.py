@@ -34,7 +34,8 @@ def test_traffic_scaling_and_json(tmp_path):
                           str(tmp_path / "write"), "--workload", "w", "--json", str(out), "--algorithmic-bytes", "123"],
                          capture_output=True, text=True, check=True)
     assert "scale 2.0000" in res.stdout and "scale 1.0000" in res.stdout
-    doc = json.loads(out.read_text())
+    doc = json.loads(out.read_text())["records"][0]
+    assert len(doc["attention_source_sha256"]) == 64
     att = doc["kernels"]["attention_kernel<128,1>"]
     assert att["launches"] == 2 and att["fetch_bytes"] == 2000 * 1024 * 2 and att["write_bytes"] == 500 * 1024
     comb = doc["kernels"]["combine_kernel<128>"]
@@ -42,6 +43,11 @@ def test_traffic_scaling_and_json(tmp_path):
     want = att["fetch_bytes"] + att["write_bytes"] + (comb["fetch_bytes"] + comb["write_bytes"]) * 1 / 2
     assert doc["attention_bytes_per_launch"] == int(want)
     assert doc["workload"] == "w" and doc["algorithmic_bytes_per_launch"] == 123
+    # a second summary of the same workload replaces the record; another workload is appended
+    for name in ("w", "w2"):
+        subprocess.run([sys.executable, "-m", "paper_2512_07350_amd.profile_summary", "traffic", str(tmp_path / "fetch"),
+                        str(tmp_path / "write"), "--workload", name, "--json", str(out)], capture_output=True, text=True, check=True)
+    assert [r["workload"] for r in json.loads(out.read_text())["records"]] == ["w", "w2"]
 
 
 def test_stats_table(tmp_path):
