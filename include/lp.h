@@ -46,9 +46,11 @@ extern "C" {
 #endif
 
 #define LP_OK 0
-#define LP_ERR_INVALID_ARG (-1) /* null pointer, bad index, bad stride, K or r out of range */
-#define LP_ERR_SHAPE (-2)       /* extent < 1, patch < 1, or patch does not divide its extent */
-#define LP_ERR_UNSUPPORTED (-3) /* head_dim not in {64, 128}, K above LP_MAX_PARTS, ...       */
+#define LP_ERR_INVALID_ARG (-1) /* null pointer, bad index, bad stride, aliased buffers       */
+#define LP_ERR_SHAPE (-2)       /* a problem statement the method does not define: extent < 1, */
+                                /* patch < 1 or not dividing its extent, K < 1, K above        */
+                                /* LP_MAX_PARTS, r outside [0, K-1] (Sec. 3.3)                 */
+#define LP_ERR_UNSUPPORTED (-3) /* head_dim not in {64, 128}, sizes past 32-bit addressing    */
 #define LP_ERR_HIP (-4)         /* a HIP call failed; see lp_last_hip_error()                 */
 #define LP_ERR_NOMEM (-5)       /* host allocation failed                                     */
 
@@ -91,9 +93,10 @@ int lp_rotation_dim(int64_t step_1based);
  * with lp_plan_destroy.  With N = D/p patches along dim: L = ceil(N/K),
  * core_k = [k L, k L + L), O = overlap_patches or floor(L r),
  * extended = [max(0, alpha - O), min(N, beta + O)), latent range = extended * p.
- * Errors: LP_ERR_INVALID_ARG (null, dim not 0..2, K < 1, r outside [0, K-1],
- * O > L (K-1)), LP_ERR_SHAPE, LP_ERR_UNSUPPORTED (K > LP_MAX_PARTS),
- * LP_ERR_NOMEM.
+ * Errors: LP_ERR_INVALID_ARG (null, dim not 0..2), LP_ERR_SHAPE (extent or patch
+ * < 1, patch not dividing its extent, K < 1, K > LP_MAX_PARTS, r outside
+ * [0, K-1] or O > L (K-1)), LP_ERR_UNSUPPORTED (latent of 2^40 elements or
+ * more), LP_ERR_NOMEM.
  */
 int lp_plan_create(const lp_config *cfg, int32_t dim, lp_plan **out);
 void lp_plan_destroy(lp_plan *plan); /* NULL is allowed */
@@ -189,6 +192,13 @@ int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_
  * probabilities are rounded to bf16 before the second product and the result is
  * rounded to bf16 on store.
  */
+ * Inputs must be finite.  With an infinity or a NaN in q, k or v the affected
+ * output rows are unspecified (typically NaN, also where the definition would
+ * give an infinity: rows of v beyond a probability of exactly 0 are still
+ * multiplied); no memory outside o is written and the call still succeeds.
+ * The workspace parameters are this library's own addition to the operation:
+ * the method defines only q, k, v -> o.  NULL keeps the call allocation- and
+ * scratch-free at the cost of idle compute units (see above).
 int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
                  int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
                  float scale, void *workspace, int64_t workspace_bytes, void *stream);

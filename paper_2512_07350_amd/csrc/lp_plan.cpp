@@ -26,8 +26,7 @@ int lp_plan_create(const lp_config *cfg, int32_t dim, lp_plan **out) {
     if (out == nullptr) return LP_ERR_INVALID_ARG;
     *out = nullptr;
     if (cfg == nullptr || dim < 0 || dim > 2) return LP_ERR_INVALID_ARG;
-    if (cfg->K < 1) return LP_ERR_INVALID_ARG;
-    if (cfg->K > LP_MAX_PARTS) return LP_ERR_UNSUPPORTED;
+    if (cfg->K < 1 || cfg->K > LP_MAX_PARTS) return LP_ERR_SHAPE;
     const int32_t ext[3] = {cfg->T, cfg->H, cfg->W};
     const int32_t pat[3] = {cfg->pT, cfg->pH, cfg->pW};
     if (cfg->C < 1) return LP_ERR_SHAPE;
@@ -47,10 +46,10 @@ int lp_plan_create(const lp_config *cfg, int32_t dim, lp_plan **out) {
         O = cfg->overlap_patches;
     } else {
         const double r = cfg->overlap_ratio;
-        if (!(r >= 0.0) || r > double(K - 1)) return LP_ERR_INVALID_ARG;
+        if (!(r >= 0.0) || r > double(K - 1)) return LP_ERR_SHAPE;   // Sec. 3.3: r in [0, K-1]
         O = static_cast<int64_t>(std::floor(double(L) * r));
     }
-    if (O > int64_t(L) * (K - 1)) return LP_ERR_INVALID_ARG;
+    if (O > int64_t(L) * (K - 1)) return LP_ERR_SHAPE;                // the same bound, for O given directly
 
     lp_plan *pl = new (std::nothrow) lp_plan();
     if (pl == nullptr) return LP_ERR_NOMEM;
@@ -118,7 +117,7 @@ const char *lp_strerror(int status) {
     switch (status) {
         case LP_OK: return "ok";
         case LP_ERR_INVALID_ARG: return "invalid argument";
-        case LP_ERR_SHAPE: return "latent extent or patch size not usable (patch must divide extent)";
+        case LP_ERR_SHAPE: return "problem statement outside what the method defines (patch must divide extent, 1 <= K <= 64, r in [0, K-1])";
         case LP_ERR_UNSUPPORTED: return "unsupported size or head_dim";
         case LP_ERR_HIP: return "HIP call failed (see lp_last_hip_error)";
         case LP_ERR_NOMEM: return "host allocation failed";
@@ -128,6 +127,6 @@ const char *lp_strerror(int status) {
 
 int lp_last_hip_error(void) { return g_last_hip_error; }
 
-const char *lp_version(void) { return "lp-mi355x 0.1 (gfx950)"; }
+const char *lp_version(void) { return "lp-mi355x 0.2 (gfx950)"; }
 
 }  // extern "C"

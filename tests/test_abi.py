@@ -100,11 +100,11 @@ def test_plan_error_codes():
         return e.value.status
     assert status((16, 5, 15, 16), (1, 2, 2), 2, 1, overlap_patches=1) == lp.LP_ERR_SHAPE
     assert status((16, 5, 16, 16), (1, 0, 2), 2, 1, overlap_patches=1) == lp.LP_ERR_SHAPE
-    assert status((16, 5, 16, 16), (1, 2, 2), 0, 1, overlap_patches=1) == lp.LP_ERR_INVALID_ARG
-    assert status((16, 5, 16, 16), (1, 2, 2), 2, 3, overlap_patches=1) == lp.LP_ERR_INVALID_ARG
-    assert status((16, 5, 16, 16), (1, 2, 2), 2, 1, overlap_ratio=1.5) == lp.LP_ERR_INVALID_ARG
-    assert status((16, 5, 16, 16), (1, 2, 2), 2, 1, overlap_patches=5) == lp.LP_ERR_INVALID_ARG
-    assert status((16, 5, 16, 16), (1, 2, 2), 65, 1, overlap_patches=0) == lp.LP_ERR_UNSUPPORTED
+    assert status((16, 5, 16, 16), (1, 2, 2), 0, 1, overlap_patches=1) == lp.LP_ERR_SHAPE          # K < 1
+    assert status((16, 5, 16, 16), (1, 2, 2), 2, 3, overlap_patches=1) == lp.LP_ERR_INVALID_ARG    # dim
+    assert status((16, 5, 16, 16), (1, 2, 2), 2, 1, overlap_ratio=1.5) == lp.LP_ERR_SHAPE          # r > K - 1
+    assert status((16, 5, 16, 16), (1, 2, 2), 2, 1, overlap_patches=5) == lp.LP_ERR_SHAPE          # O > L (K - 1)
+    assert status((16, 5, 16, 16), (1, 2, 2), 65, 1, overlap_patches=0) == lp.LP_ERR_SHAPE         # K > LP_MAX_PARTS
     plan = lp.lp_plan_create((16, 5, 16, 16), (1, 2, 2), 2, 1, overlap_patches=1)
     with pytest.raises(lp.LPError):
         lp.lp_plan_query(plan, 2)
