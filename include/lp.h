@@ -53,6 +53,7 @@ extern "C" {
 #define LP_ERR_UNSUPPORTED (-3) /* head_dim not in {64, 128}, sizes past 32-bit addressing    */
 #define LP_ERR_HIP (-4)         /* a HIP call failed; see lp_last_hip_error()                 */
 #define LP_ERR_NOMEM (-5)       /* host allocation failed                                     */
+#define LP_ERR_LIMIT (-6)       /* beyond the fixed scratch of a non-allocating entry point   */
 
 #define LP_MAX_PARTS 64
 
@@ -191,7 +192,6 @@ int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_
  * scale*log2(e) and re-rounded to bf16 once; the softmax is binary32;
  * probabilities are rounded to bf16 before the second product and the result is
  * rounded to bf16 on store.
- */
  * Inputs must be finite.  With an infinity or a NaN in q, k or v the affected
  * output rows are unspecified (typically NaN, also where the definition would
  * give an infinity: rows of v beyond a probability of exactly 0 are still
@@ -199,6 +199,7 @@ int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_
  * The workspace parameters are this library's own addition to the operation:
  * the method defines only q, k, v -> o.  NULL keeps the call allocation- and
  * scratch-free at the cost of idle compute units (see above).
+ */
 int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
                  int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
                  float scale, void *workspace, int64_t workspace_bytes, void *stream);
@@ -224,6 +225,24 @@ int lp_attention_batch(const void *q, const void *k, const void *v, void *o, int
  * 128 on 256 compute units).  Negative LP_ERR_* on failure.
  */
 int64_t lp_attention_workspace_size(int32_t head_dim);
+
+/*
+ * lp_attention for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same kernels, with the scratch for shared query tiles taken from a fixed array that
+ * lives in the library's device image (lp_attention_static_scratch_bytes() bytes, about
+ * 35 MB, held by every device the library runs on until the process ends).  Arguments,
+ * results and errors as lp_attention without its workspace pair.  The call allocates and
+ * frees nothing; its first call on a device looks the array's address up once.
+ * LP_ERR_LIMIT if the device has more compute units than the array has slots for
+ * (2 per compute unit, 256 compute units at head_dim 128).
+ * All calls on one device share the one array: calls that overlap in time on the same
+ * device (two streams, two threads) race on it and must be serialised by the caller.
+ */
+int lp_attention_static(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
+                        int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
+                        float scale, void *stream);
+int64_t lp_attention_static_scratch_bytes(void); /* size of that array, bytes */
 
 const char *lp_strerror(int status); /* static string, never NULL              */
 int lp_last_hip_error(void);         /* hipError_t of the last LP_ERR_HIP (thread local) */

@@ -25,6 +25,7 @@ LP_ERR_SHAPE = -2
 LP_ERR_UNSUPPORTED = -3
 LP_ERR_HIP = -4
 LP_ERR_NOMEM = -5
+LP_ERR_LIMIT = -6
 LP_MAX_PARTS = 64
 
 # every symbol include/lp.h declares
@@ -32,7 +33,8 @@ EXPORTS = (
     "lp_rotation_dim", "lp_plan_create", "lp_plan_destroy", "lp_plan_num_parts", "lp_plan_dim",
     "lp_plan_total_elems", "lp_plan_latent_elems", "lp_plan_query", "lp_partition", "lp_reconstruct",
     "lp_reconstruct_guided_step", "lp_reconstruct_guided_step_partition",
-    "lp_attention", "lp_attention_batch", "lp_attention_workspace_size", "lp_strerror", "lp_last_hip_error", "lp_version",
+    "lp_attention", "lp_attention_batch", "lp_attention_workspace_size", "lp_attention_static",
+    "lp_attention_static_scratch_bytes", "lp_strerror", "lp_last_hip_error", "lp_version",
 )
 
 
@@ -102,6 +104,10 @@ def _lib():
         lib.lp_attention.restype = C.c_int
         lib.lp_attention_batch.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i64, i64, i64, C.c_float, vp, i64, vp]
         lib.lp_attention_batch.restype = C.c_int
+        lib.lp_attention_static.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, i64, C.c_float, vp]
+        lib.lp_attention_static.restype = C.c_int
+        lib.lp_attention_static_scratch_bytes.argtypes = []
+        lib.lp_attention_static_scratch_bytes.restype = i64
         lib.lp_attention_workspace_size.argtypes = [i32]
         lib.lp_attention_workspace_size.restype = i64
         lib.lp_strerror.argtypes = [C.c_int]
@@ -256,3 +262,13 @@ def lp_attention_batch(q, k, v, o, batch: int, n_tokens: int, heads: int, head_d
     _check(_lib().lp_attention_batch(_ptr(q), _ptr(k), _ptr(v), _ptr(o), int(batch), int(n_tokens), int(heads),
                                      int(head_dim), int(stride_batch), int(stride_tok), int(stride_head), float(scale),
                                      _ptr(workspace) or None, int(workspace_bytes), stream or None), "lp_attention_batch")
+
+
+def lp_attention_static(q, k, v, o, n_tokens: int, heads: int, head_dim: int, stride_tok: int, stride_head: int,
+                        scale: float = 0.0, stream: Optional[int] = None) -> None:
+    _check(_lib().lp_attention_static(_ptr(q), _ptr(k), _ptr(v), _ptr(o), int(n_tokens), int(heads), int(head_dim),
+                                      int(stride_tok), int(stride_head), float(scale), stream or None), "lp_attention_static")
+
+
+def lp_attention_static_scratch_bytes() -> int:
+    return int(_lib().lp_attention_static_scratch_bytes())

@@ -857,12 +857,16 @@ extern "C" int64_t lp_attention_workspace_size(int32_t head_dim) {
 
 namespace {
 
-int attention_call(const void *q, const void *k, const void *v, void *o, int32_t batch, int64_t n_tokens, int32_t heads,
-                   int32_t head_dim, int64_t stride_batch, int64_t stride_tok, int64_t stride_head, float scale,
-                   void *workspace, int64_t workspace_bytes, void *stream) {
+// Argument checks shared by the entry points; no HIP call.  LP_OK: launch; kNothingToDo: succeed
+// without a launch; negative: the error to return.
+constexpr int kNothingToDo = 1;
+
+int attention_check(const void *q, const void *k, const void *v, void *o, int32_t batch, int64_t n_tokens, int32_t heads,
+                    int32_t head_dim, int64_t stride_batch, int64_t stride_tok, int64_t stride_head,
+                    void *workspace, int64_t workspace_bytes) {
     if (n_tokens < 0 || heads < 1 || batch < 1) return LP_ERR_INVALID_ARG;
     if (head_dim != 64 && head_dim != 128) return LP_ERR_UNSUPPORTED;
-    if (n_tokens == 0) return LP_OK;
+    if (n_tokens == 0) return kNothingToDo;
     if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return LP_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return LP_ERR_INVALID_ARG;
     if (o == q || o == k || o == v) return LP_ERR_INVALID_ARG;   // the output is written while inputs are still read
@@ -886,6 +890,16 @@ int attention_call(const void *q, const void *k, const void *v, void *o, int32_t
     if (all_heads >= (int64_t(1) << 24)) return LP_ERR_UNSUPPORTED;
     const int64_t units = all_heads * ((n_tokens + kBM - 1) / kBM);
     if (units * ((n_tokens + kBN - 1) / kBN + kBoundaryTiles) >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
+    return LP_OK;
+}
+
+int attention_call(const void *q, const void *k, const void *v, void *o, int32_t batch, int64_t n_tokens, int32_t heads,
+                   int32_t head_dim, int64_t stride_batch, int64_t stride_tok, int64_t stride_head, float scale,
+                   void *workspace, int64_t workspace_bytes, void *stream) {
+    const int chk = attention_check(q, k, v, o, batch, n_tokens, heads, head_dim, stride_batch, stride_tok, stride_head,
+                                    workspace, workspace_bytes);
+    if (chk != LP_OK) return chk == kNothingToDo ? LP_OK : chk;
+    const int64_t all_heads = int64_t(batch) * heads;
     if (!(scale > 0.0f)) scale = 1.0f / sqrtf(float(head_dim));
     AttnParams a{};
     a.q = static_cast<const __bf16 *>(q);
@@ -904,6 +918,70 @@ int attention_call(const void *q, const void *k, const void *v, void *o, int32_t
 }
 
 }  // namespace
+
+// ---- scratch for callers that cannot allocate (lp_attention_static)
+// Sized for the partial-result slots of head_dim 128 on kStaticMaxCUs compute units (the
+// largest case; head_dim 64 needs less).  Every device the library runs on holds its own copy
+// of this array, at its own address, until the process ends.  In host code the array's name
+// is only a handle for hipGetSymbolAddress: kernels are given the address that call returns.
+constexpr int kStaticMaxCUs = 256;
+constexpr size_t kStaticScratchFloats = size_t(2) * kStaticMaxCUs * slot_floats<128>();
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<float *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device; looked up once per device, with that
+// device current.  Returns nullptr (and records the HIP error) on failure.
+float *static_scratch(int *status) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        lp::set_last_hip_error(int(e));
+        *status = LP_ERR_HIP;
+        return nullptr;
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+        *status = LP_ERR_LIMIT;
+        return nullptr;
+    }
+    float *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void *sym = nullptr;
+        e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || sym == nullptr) {
+            lp::set_last_hip_error(int(e));
+            *status = LP_ERR_HIP;
+            return nullptr;
+        }
+        p = static_cast<float *>(sym);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // a racing thread stores the same address
+    }
+    *status = LP_OK;
+    return p;
+}
+
+}  // namespace
+
+extern "C" int64_t lp_attention_static_scratch_bytes(void) { return int64_t(kStaticScratchFloats * sizeof(float)); }
+
+extern "C" int lp_attention_static(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
+                                   int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,
+                                   float scale, void *stream) {
+    const int chk = attention_check(q, k, v, o, 1, n_tokens, heads, head_dim, 0, stride_tok, stride_head, nullptr, 0);
+    if (chk != LP_OK) return chk == kNothingToDo ? LP_OK : chk;
+    const int cus = device_compute_units();
+    if (cus <= 0) return LP_ERR_HIP;
+    // the slots of every compute unit must fit the fixed array
+    const int64_t need = head_dim == 128 ? workspace_bytes_for<128>(cus) : workspace_bytes_for<64>(cus);
+    if (need > int64_t(kStaticScratchFloats * sizeof(float))) return LP_ERR_LIMIT;
+    int status = LP_OK;
+    float *ws = static_scratch(&status);
+    if (ws == nullptr) return status;
+    return attention_call(q, k, v, o, 1, n_tokens, heads, head_dim, 0, stride_tok, stride_head, scale, ws, need, stream);
+}
 
 extern "C" int lp_attention(const void *q, const void *k, const void *v, void *o, int64_t n_tokens,
                             int32_t heads, int32_t head_dim, int64_t stride_tok, int64_t stride_head,

@@ -121,6 +121,7 @@ const char *lp_strerror(int status) {
         case LP_ERR_UNSUPPORTED: return "unsupported size or head_dim";
         case LP_ERR_HIP: return "HIP call failed (see lp_last_hip_error)";
         case LP_ERR_NOMEM: return "host allocation failed";
+        case LP_ERR_LIMIT: return "request exceeds the fixed scratch of the non-allocating entry point";
         default: return "unknown status";
     }
 }

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_strerror():
     assert "gfx950" in lp.lp_version()
     assert lp.lp_strerror(0) == "ok"
-    for code in (-1, -2, -3, -4, -5, -99):
+    for code in (-1, -2, -3, -4, -5, -6, -99):
         assert lp.lp_strerror(code)
 
 
@@ -134,6 +134,11 @@ def test_device_calls_reject_bad_arguments_without_a_gpu():
     assert lib.lp_reconstruct(plan.handle, 16, 16, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_reconstruct_guided_step(plan.handle, 16, 32, 1.0, 48, 1.0, 1.0, 32, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention_workspace_size(96) == lp.LP_ERR_UNSUPPORTED
+    # the non-allocating variant checks its arguments the same way, before anything touches a device
+    assert lib.lp_attention_static(16, 32, 48, 64, 10, 4, 96, 384, 96, 0.0, None) == lp.LP_ERR_UNSUPPORTED
+    assert lib.lp_attention_static(16, 32, 48, 16, 10, 4, 64, 256, 64, 0.0, None) == lp.LP_ERR_INVALID_ARG
+    assert lib.lp_attention_static(None, None, None, None, 0, 4, 64, 256, 64, 0.0, None) == lp.LP_OK
+    assert lib.lp_attention_static_scratch_bytes() == 2 * 256 * 256 * (128 // 2 + 2) * 4
     # batch: items must not overlap (outer: stride_batch >= one item; inner: fits between token and head strides)
     assert lib.lp_attention_batch(16, 32, 48, 64, 0, 10, 4, 64, 0, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention_batch(16, 32, 48, 64, 2, 10, 4, 64, 1280, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
