@@ -4,15 +4,20 @@
 // gfx950: bf16 MFMA 32x32x16 for both products, binary32 online softmax, K and V
 // tiles streamed global -> LDS without passing through registers.
 //
-// Work decomposition.  One workgroup = 8 wavefronts = 256 query rows of one head;
-// each wavefront owns 32 query rows (one 32-column MFMA block) and walks all keys
-// in rounds of 32.  Per round it forms the TRANSPOSED scores
+// Work decomposition.  One workgroup = 4 wavefronts = 256 query rows of one head, one
+// wavefront per SIMD; each wavefront owns 64 query rows (two 32-column MFMA blocks) and
+// walks all keys in rounds of 32.  Per round it forms the TRANSPOSED scores
 //     S^T[key, query] = K . Q^T            (A = K rows from LDS, B = Q in registers)
 // so that in the MFMA accumulator layout a lane holds 16 scores of ONE query: the
 // row maximum and row sum are in-lane reductions, the rescale factor of the running
 // output is a per-lane scalar, and the bf16 probabilities are already laid out as
 // the B operand of
 //     O^T[d, query] += V^T . P^T           (A = V^T, read transposed from LDS).
+// Every operand fetched from LDS feeds two products (one per 32-query block): 0.75 LDS
+// reads per matrix instruction.  The 64 rows need more than 256 registers per lane: the
+// O^T accumulators and the Q^T operands are kept in the accumulation registers (AGPRs) by
+// writing the matrix instructions as assembly statements with the register file of every
+// operand spelled out (see mfma_score / mfma_pv).
 //
 // Details that matter for speed:
 //  * Q is multiplied by scale*log2(e) once and re-rounded to bf16, and the score
@@ -21,8 +26,10 @@
 //  * The running maximum is only raised when some score exceeds it by more than
 //    kRescaleThreshold; probabilities then stay below 2^kRescaleThreshold and the
 //    output accumulators are rescaled in a rarely taken, wave-uniform branch.
-//  * The score product of round r+1 is issued before the softmax of round r, so
-//    MFMA and VALU work of one wavefront overlap.
+//  * The score product of round r+1, the softmax of round r and the PV product of round
+//    r-1 share one step, and the step's vector and LDS work is cut into one small window
+//    per matrix instruction (pipeline_step), so that the one wavefront of a SIMD has its
+//    next product ready when the matrix pipeline takes it.
 //  * The key order inside a 32-key round is permuted (bits 2 and 3 of the MFMA row
 //    index swapped when K rows are read) so that the 8 probabilities a lane feeds
 //    to one MFMA belong to 8 consecutive keys; V^T operands then come from two
@@ -38,6 +45,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "lp_internal.h"
 
@@ -53,10 +61,21 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 #define LP_LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 
+// f(integral_constant<int, I>) for I = FROM .. TO-1: a loop whose index is a constant
+// expression inside the body.
+template <int FROM, int TO, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (FROM < TO) {
+        f(std::integral_constant<int, FROM>{});
+        static_for<FROM + 1, TO>(f);
+    }
+}
+
 constexpr int kBM = 256;                      // query rows per workgroup
 // A wavefront owns NB blocks of 32 query rows; the workgroup has kBM / (32 NB) wavefronts.
 constexpr int waves_of(int nb) { return kBM / (32 * nb); }
-constexpr int kBlocksPerWave = 1;             // NB used by lp_attention
+// NB used by lp_attention: 64 query rows per wavefront (one wavefront per SIMD, four per workgroup)
+constexpr int blocks_per_wave(int d) { return 2; }
 constexpr int kBN = 64;                       // keys per LDS tile (two rounds of 32)
 constexpr int kStages = 4;                    // LDS stages: three tiles in use plus one arriving
 constexpr float kRescaleThreshold = 8.0f;     // log2 units the running max may lag behind
@@ -103,6 +122,14 @@ __device__ __forceinline__ void wait_tile_loads() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory");
 }
 
+// At most N LDS operations of this wavefront still outstanding (the compiler sees this wait
+// and leaves out its own for everything older).
+template <int N>
+__device__ __forceinline__ void lds_wait() {
+    static_assert(N >= 0 && N < 16, "lgkmcnt range");
+    __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+}
+
 // LDS accesses below use 32-bit LDS byte addresses held in registers.
 // The same value, but not a loop invariant as far as the compiler can tell.
 __device__ __forceinline__ int opaque(int x) {
@@ -113,6 +140,12 @@ __device__ __forceinline__ int opaque(int x) {
 template <typename V>
 __device__ __forceinline__ V lds_load(uint32_t addr) {
     return *LP_LDS_PTR(const V, uintptr_t(addr));
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
 }
 
 __device__ __forceinline__ float max16(const f32x16 &s) {
@@ -144,11 +177,18 @@ struct Lane {
 // of the tile just sent for in front of the operand reads of the tiles in use.  The waits that
 // order these loads against the reads of their own stage are wait_tile_loads + barrier.
 // Nothing else in this file uses M0.
-__device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory", "m0");
+template <int V_LDS_OFFSET>
+__device__ __forceinline__ void load_kv_to_lds_16(__amdgpu_buffer_rsrc_t k_rsrc, __amdgpu_buffer_rsrc_t v_rsrc, uint32_t k_lds,
+                                                  uint32_t k_voff, uint32_t v_voff, uint32_t soff) {
+    // K block, then the V block V_LDS_OFFSET bytes further on.  M0 must be written one
+    // instruction before the load that uses it: the address of the V block is formed between
+    // the first write and its use, an s_nop stands between the second write and its use.
+    uint32_t v_lds;
+    asm volatile("s_mov_b32 m0, %1\n\ts_add_u32 %0, %1, %2\n\tbuffer_load_dwordx4 %3, %5, %7 offen lds\n\t"
+                 "s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %4, %6, %7 offen lds"
+                 : "=&s"(v_lds)
+                 : "s"(k_lds), "n"(V_LDS_OFFSET), "v"(k_voff), "v"(v_voff), "s"(k_rsrc), "s"(v_rsrc), "s"(soff)
+                 : "memory", "m0", "scc");
 }
 
 // global -> LDS loads of one K/V tile into the stage at byte offset stage_off.  One
@@ -161,8 +201,7 @@ __device__ __forceinline__ void issue_tile(uint32_t lds0, const Lane<D, NB> &c, 
 #pragma unroll
     for (int i = 0; i < Lane<D, NB>::kLd; ++i) {
         const uint32_t dst_k = __builtin_amdgcn_readfirstlane(lds0 + stage_off + c.ld_dst[i]);
-        load_to_lds_16(c.k_rsrc, dst_k, c.k_voff[i], soff);
-        load_to_lds_16(c.v_rsrc, dst_k + T::kTileBytes, c.v_voff[i], soff);
+        load_kv_to_lds_16<T::kTileBytes>(c.k_rsrc, c.v_rsrc, dst_k, c.k_voff[i], c.v_voff[i], soff);
     }
 }
 
@@ -180,26 +219,67 @@ __device__ __forceinline__ void mask_scores(int r, int half, int n, f32x16 (&s)[
     }
 }
 
-// bf16 probabilities exp2(s) laid out as PV operands (the scores are already relative to the
-// running maximum); the row sum adds the rounded values.
+// ---- the matrix instructions, with the register file of every operand chosen here.
+// A wavefront that owns 64 query rows needs more than 256 registers: the O^T accumulators
+// (D/32 * NB * 16) and the Q^T operands (NB * D/16 * 4) live in the accumulation registers
+// (AGPRs) and are touched by matrix instructions only; scores, probabilities and the LDS
+// operands live in the ordinary ones, where the vector ALU works on them.  The compiler is
+// not told what these statements are, so it neither moves operands between the two files
+// nor inserts the wait states that separate a matrix instruction's result from a vector
+// instruction reading it; settle_scores / settle_acc below do that where such a read follows.
+__device__ __forceinline__ void mfma_score_init(f32x16 &d, const bf16x8 &k, const bf16x8 &q, const f32x16 &c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d) : "v"(k), "a"(q), "v"(c));
+}
+__device__ __forceinline__ void mfma_score(f32x16 &d, const bf16x8 &k, const bf16x8 &q) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(k), "a"(q));
+}
+__device__ __forceinline__ void mfma_pv(f32x16 &acc, const bf16x8 &vt, const bf16x8 &p) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(vt), "v"(p));
+}
+
+// Ordering points for the vector work between matrix instructions.  Statements of this kind
+// keep their program order among themselves, so whatever produces x comes before this point
+// and whatever uses x afterwards comes after it; no instruction is emitted.
+__device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(f32x2 &x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(uint32_t &x) { asm volatile("" : "+v"(x)); }
+
+// Scores written by matrix instructions become readable by vector instructions: 16 wait
+// states cover the 8 passes of the last product plus its write-back.
 template <int NB>
-__device__ __forceinline__ void probabilities(const f32x16 (&s)[NB], bf16x8 (&p)[NB][2], float (&l_run)[NB]) {
+__device__ __forceinline__ void settle_scores(f32x16 (&s)[NB], bool wait) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        Pack16 lo, hi;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-        float l = l_run[nb];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            lo.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][2 * e]), __builtin_amdgcn_exp2f(s[nb][2 * e + 1]));
-            hi.p[e] = to_bf16x2(__builtin_amdgcn_exp2f(s[nb][8 + 2 * e]), __builtin_amdgcn_exp2f(s[nb][8 + 2 * e + 1]));
-            l = __builtin_amdgcn_fdot2_f32_bf16(lo.p[e], ones, l, false);
-            l = __builtin_amdgcn_fdot2_f32_bf16(hi.p[e], ones, l, false);
-        }
-        l_run[nb] = l;
-        p[nb][0] = lo.v;
-        p[nb][1] = hi.v;
+        if (wait) asm volatile("s_nop 15" : "+v"(s[nb]));
+        else asm volatile("" : "+v"(s[nb]));
     }
+}
+
+// The same for the accumulators in the AGPRs (before they are rescaled or stored), and, with
+// after = true, between vector writes to them and the next matrix instruction.
+template <int D, int NB>
+__device__ __forceinline__ void settle_acc(f32x16 (&acc)[D / 32][NB], bool after) {
+    if (after) asm volatile("s_nop 3");
+    else asm volatile("s_nop 15\n\ts_nop 7");
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+a"(acc[mb][nb]));
+}
+
+// Two scores (already relative to the running maximum) -> one packed pair of bf16 probabilities.
+__device__ __forceinline__ uint32_t probability_pair(const f32x2 &s) {
+    union { bf16x2 p; uint32_t u; } w;
+    w.p = to_bf16x2(__builtin_amdgcn_exp2f(s[0]), __builtin_amdgcn_exp2f(s[1]));
+    return w.u;
+}
+
+// The row sum adds the rounded probabilities.
+__device__ __forceinline__ void add_to_row_sum(uint32_t pair, float &l) {
+    union { bf16x2 p; uint32_t u; } w;
+    w.u = pair;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    l = __builtin_amdgcn_fdot2_f32_bf16(w.p, ones, l, false);
 }
 
 // Lazy running maximum.  Score accumulators start at neg_m = -m (m = running maximum, log2
@@ -208,15 +288,16 @@ __device__ __forceinline__ void probabilities(const f32x16 (&s)[NB], bf16x8 (&p)
 // under the old one: these scores, the output accumulators, the row sums, and the
 // probabilities p_pending that have been computed but not yet multiplied into acc.
 template <int D, int NB>
-__device__ __forceinline__ void raise_maximum(f32x16 (&s)[NB], f32x16 (&neg_m)[NB], bf16x8 (&p_pending)[NB][2],
-                                              f32x16 (&acc)[D / 32][NB], float (&l_run)[NB]) {
+__device__ __forceinline__ void raise_maximum(const float (&lane_max)[NB], f32x16 (&s)[NB], f32x16 (&neg_m)[NB],
+                                              bf16x8 (&p_pending)[NB][2], f32x16 (&acc)[D / 32][NB], float (&l_run)[NB]) {
     bool raise = false;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) raise = raise || (max16(s[nb]) > kRescaleThreshold);
+    for (int nb = 0; nb < NB; ++nb) raise = raise || (lane_max[nb] > kRescaleThreshold);
     if (__any(raise)) {
+        settle_acc<D, NB>(acc, false);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            float tmax = max16(s[nb]);
+            float tmax = lane_max[nb];
             tmax = fmaxf(tmax, other_half(tmax));
             const float delta = fmaxf(tmax, 0.0f);           // the maximum never goes down
             const float alpha = __builtin_amdgcn_exp2f(-delta);
@@ -241,6 +322,7 @@ __device__ __forceinline__ void raise_maximum(f32x16 (&s)[NB], f32x16 (&neg_m)[N
                 p_pending[nb][ks] = t.v;
             }
         }
+        settle_acc<D, NB>(acc, true);
     }
 }
 
@@ -254,16 +336,13 @@ __device__ __forceinline__ bf16x8 load_k_operand(const uint32_t (&k_addr)[D / 16
 // One V^T operand via two transposing reads.  Inside a group of 16 lanes, lane j supplies
 // the 8-byte chunk (row j/4, columns 4*(j%4)..+3) and receives column j of that 4x16 block,
 // i.e. 4 consecutive keys of one d.  Operand j covers keys 16*(j / MB).. of the round and
-// rows 32*(j % MB).. of O^T.
-template <int D, int NB, int SUB>
-__device__ __forceinline__ bf16x8 load_v_operand(const uint32_t (&v_addr)[D / 32], int j) {
+// rows 32*(j % MB).. of O^T; HALF selects its first or second four keys.
+template <int D, int NB, int SUB, int HALF>
+__device__ __forceinline__ bf16x4 load_v_half(const uint32_t (&v_addr)[D / 32], int j) {
     using T = Tile<D, NB>;
     constexpr int MB = D / 32;
-    const uint32_t a0 = v_addr[j % MB] + (SUB * 32 + (j / MB) * 16) * T::kRowBytes;
-    Pack16 a;
-    a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, uintptr_t(a0)));
-    a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, uintptr_t(a0 + 4 * T::kRowBytes)));
-    return a.v;
+    const uint32_t a0 = v_addr[j % MB] + (SUB * 32 + (j / MB) * 16 + HALF * 4) * T::kRowBytes;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LP_LDS_PTR(bf16x4, uintptr_t(a0)));
 }
 
 // Everything one wavefront carries from step to step.
@@ -288,8 +367,8 @@ struct Pipe {
 // d = 32*mb + 8*(i/4) + 4*half + i%4 of O^T, i.e. 8-byte pieces of many rows; the pieces
 // pass through the wave's own 4 KB of LDS (64 d at a time, 16-byte granules XORed with
 // the row so that both directions are conflict free) and leave as whole 128-byte lines.
-template <int D>
-__device__ __forceinline__ void store_rows(uint32_t out_lds, const f32x16 (&acc)[D / 32][1], float inv, __bf16 *dst,
+template <int D, int NB>
+__device__ __forceinline__ void store_rows(uint32_t out_lds, const f32x16 (&acc)[D / 32][NB], int nb, float inv, __bf16 *dst,
                                            int64_t row_stride, int rows_valid, int lane) {
     const int col = lane % 32, half = lane / 32;
 #pragma unroll
@@ -298,7 +377,7 @@ __device__ __forceinline__ void store_rows(uint32_t out_lds, const f32x16 (&acc)
         for (int mbl = 0; mbl < 2; ++mbl)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const f32x16 &x = acc[2 * pass + mbl][0];
+                const f32x16 &x = acc[2 * pass + mbl][nb];
                 union { u32x2 u; bf16x2 p[2]; } ow;
                 ow.p[0] = to_bf16x2(x[4 * g + 0] * inv, x[4 * g + 1] * inv);
                 ow.p[1] = to_bf16x2(x[4 * g + 2] * inv, x[4 * g + 3] * inv);
@@ -313,6 +392,32 @@ __device__ __forceinline__ void store_rows(uint32_t out_lds, const f32x16 (&acc)
     }
 }
 
+// The part of the softmax that trails the exponentials: converts the pairs [CVT_FROM, CVT_TO)
+// to packed bf16 words (and completes an operand with its fourth word), then adds the words
+// [SUM_FROM, CVT_FROM) to the row sums.  Pair k holds scores 2 k, 2 k + 1 counted across both
+// blocks: word k % 4 of operand (k % 8) / 4 of block k / 8.
+template <int NB, int CVT_TO, int CVT_FROM, int SUM_FROM>
+__device__ __forceinline__ void vector_tail(const float (&ex)[NB * 16], uint32_t (&pw)[NB][2][4], bf16x8 (&p_cur)[NB][2],
+                                            float (&l_run)[NB]) {
+    static_for<CVT_FROM, CVT_TO>([&](auto kc) {
+        constexpr int k = decltype(kc)::value, nb = k / 8, part = (k % 8) / 4, e = k % 4;
+        union { bf16x2 p; uint32_t u; } cv;
+        cv.p = to_bf16x2(ex[2 * k], ex[2 * k + 1]);
+        pw[nb][part][e] = cv.u;
+        pin(pw[nb][part][e]);
+        if constexpr (e == 3) {
+            Pack16 t;
+            t.u = make_uint4(pw[nb][part][0], pw[nb][part][1], pw[nb][part][2], pw[nb][part][3]);
+            p_cur[nb][part] = t.v;
+        }
+    });
+    static_for<SUM_FROM, CVT_FROM>([&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        add_to_row_sum(pw[k / 8][(k % 8) / 4][k % 4], l_run[k / 8]);
+        pin(l_run[k / 8]);
+    });
+}
+
 template <int BYTES>
 __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
     off += BYTES;
@@ -321,11 +426,12 @@ __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
 
 // Step i of the software pipeline (SUB = i % 2).  For ONE wavefront a step issues
 //   MFMA:  S^T of round i+1, then O^T += V^T P^T of round i-1
-//   VALU:  probabilities of round i, then the maximum check for round i+1
-//   LDS :  each score MFMA is followed by the fetch of a V operand of round i-1 into the
-//          registers it has just read, each PV MFMA by the fetch of a K operand of round i+2
-// so that matrix and vector work of the same wavefront overlap, an LDS operand is fetched
-// half a step before its product, and K and V operands share one set of registers.
+//   VALU:  probabilities of round i (spread over the whole step), then the maximum check
+//          for round i+1
+//   LDS :  each score group is followed by the fetch of a V operand of round i-1 into the
+//          registers it has just read, each PV group by the fetch of a K operand of round i+2
+// so that an LDS operand is fetched half a step before its products, and K and V operands
+// share one set of registers.
 // Even steps open tile t+1 (t = i/2): they wait for its loads, pass the barrier (after which
 // every wave has fetched its last operand from tile t-2), and refill that stage with tile
 // t+kStages-2.
@@ -364,23 +470,81 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
         }
     }
 
-#pragma unroll
-    for (int j = 0; j < KS; ++j) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            s_nxt[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], w.qreg[nb][j], j == 0 ? w.neg_m[nb] : s_nxt[nb], 0, 0, 0);
-        w.opreg[j] = load_v_operand<D, NB, 1 - SUB>(w.v_addr, j);
-    }
-    probabilities<NB>(s_cur, p_cur, w.l_run);
-#pragma unroll
-    for (int j = 0; j < KS; ++j) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            w.acc[j % MB][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[j], p_prev[nb][j / MB], w.acc[j % MB][nb], 0, 0, 0);
-        w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
-    }
-    if (MASK) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
-    raise_maximum<D, NB>(s_nxt, w.neg_m, p_cur, w.acc, w.l_run);
+    // The step's 2 KS NB products, in KS score groups and then KS PV groups (a group is the
+    // NB products that share one LDS operand).  The wavefront is alone on its SIMD, so the
+    // matrix pipeline is busy only if the next product is issued within the 8 passes of the
+    // one before: the vector and LDS work of the step is therefore cut into one window per
+    // product -- the exponentials of round i (8 / KS per window), a conversion and a row-sum
+    // update for every second of them, the refill of the operand registers the group has just
+    // read (half a V^T operand or one K operand per window), and, over the last KS/2 groups,
+    // the per-lane maximum of round i+1's scores, whose products have long left the pipeline.
+    static_assert(NB == 2, "the windows below are laid out for two 32-row blocks per wavefront");
+    constexpr int M = 2 * KS * NB;              // products per step
+    constexpr int X = (NB * 16) / M;            // exponentials per window
+    constexpr int kMaxFrom = (KS + KS / 2) * NB, kMaxPer = 16 / (KS / 2);
+    uint32_t pw[NB][2][4];
+    float ex[NB * 16];
+    float lane_max[NB];
+    Pack16 vop;
+    static_for<0, M>([&](auto mc) {
+        constexpr int m = decltype(mc)::value, g = m / NB, nb = m % NB;
+        // Operand arrivals are checked for half a phase at a time.  In issue order the LDS queue
+        // holds, at the start of the score phase, the KS K fetches of the previous PV phase: all
+        // but the newest KS/2 cover groups 0 .. KS/2-1; by group KS/2 the newest are KS/2 groups
+        // of V fetches (2 each), so lgkmcnt(KS) covers the rest.  The PV phase mirrors this with
+        // 2 KS V fetches followed by one K fetch per group.
+        if constexpr (nb == 0 && g == 0) lds_wait<KS / 2>();
+        if constexpr (nb == 0 && g == KS / 2) lds_wait<KS>();
+        if constexpr (nb == 0 && g == KS) lds_wait<KS>();
+        if constexpr (nb == 0 && g == KS + KS / 2) lds_wait<KS / 2>();
+        if constexpr (g < KS) {
+            if constexpr (g == 0) mfma_score_init(s_nxt[nb], w.opreg[g], w.qreg[nb][g], w.neg_m[nb]);
+            else mfma_score(s_nxt[nb], w.opreg[g], w.qreg[nb][g]);
+            if constexpr (nb == 0) vop.h[0] = load_v_half<D, NB, 1 - SUB, 0>(w.v_addr, g);
+            else {
+                vop.h[1] = load_v_half<D, NB, 1 - SUB, 1>(w.v_addr, g);
+                w.opreg[g] = vop.v;
+            }
+        } else {
+            constexpr int j = g - KS;
+            mfma_pv(w.acc[j % MB][nb], w.opreg[j], p_prev[nb][j / MB]);
+            if constexpr (nb == NB - 1) w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
+        }
+        // exponentials x = m X .. of the round's NB * 16 scores.  A pair is converted in the
+        // window after its second exponential (a conversion must not directly follow the
+        // exponential it reads) and joins the row sum one window later.
+        static_for<m * X, (m + 1) * X>([&](auto xc) {
+            constexpr int x = decltype(xc)::value;
+            float sc = s_cur[x / 16][x % 16];
+            pin(sc);
+            ex[x] = __builtin_amdgcn_exp2f(sc);
+        });
+        vector_tail<NB, m * X / 2, (m > 0 ? (m - 1) * X / 2 : 0), (m > 1 ? (m - 2) * X / 2 : 0)>(ex, pw, p_cur, w.l_run);
+        static_for<m * X, (m + 1) * X>([&](auto xc) { pin(ex[decltype(xc)::value]); });
+        if constexpr (m == kMaxFrom - 1) {
+            settle_scores<NB>(s_nxt, false);
+            if (MASK) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
+        }
+        if constexpr (m >= kMaxFrom) {
+            constexpr int wdx = m - kMaxFrom, nbm = wdx % NB, first = (wdx / NB) * kMaxPer;
+            // three-operand maxima, written out so that no operand is first passed through a
+            // quieting v_max (the scores come from assembly statements, so the compiler cannot
+            // tell that they are ordinary numbers)
+            float mx = first == 0 ? s_nxt[nbm][0] : lane_max[nbm];
+            constexpr int lo = first == 0 ? 1 : first, hi = first + kMaxPer;
+            static_for<0, (hi - lo) / 2>([&](auto rc) {
+                constexpr int r = lo + 2 * decltype(rc)::value;
+                mx = max3(mx, s_nxt[nbm][r], s_nxt[nbm][r + 1]);
+            });
+            if constexpr ((hi - lo) % 2 == 1) mx = max3(mx, s_nxt[nbm][hi - 1], s_nxt[nbm][hi - 1]);
+            lane_max[nbm] = mx;
+            pin(lane_max[nbm]);
+        }
+    });
+    // what the last two windows left to convert and to add
+    vector_tail<NB, NB * 8, (M - 1) * X / 2, (M - 2) * X / 2>(ex, pw, p_cur, w.l_run);
+    vector_tail<NB, NB * 8, NB * 8, (M - 1) * X / 2>(ex, pw, p_cur, w.l_run);
+    raise_maximum<D, NB>(lane_max, s_nxt, w.neg_m, p_cur, w.acc, w.l_run);
 }
 
 // Launch parameters.  A unit is one 256-row query tile of one head; every unit walks
@@ -604,6 +768,14 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                 for (int r = 0; r < 16; ++r) w.acc[mb][nb][r] = 0.0f;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) w.l_run[nb] = 0.0f;
+        // the Q^T operands now live in AGPRs for the whole segment (left to itself the register
+        // allocator may keep them elsewhere and copy each into one shared AGPR quad right before
+        // its product, overwriting the quad the product issued just before is still reading)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+a"(w.qreg[nb][kk]));
+        settle_acc<D, NB>(w.acc, true);
 
         // ---- LDS operand addresses in stage 0 (recomputed from an opaque copy of the lane
         // index: kept as loop invariants they would be held in registers through the pipeline)
@@ -640,10 +812,13 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    s_a[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.opreg[kk], w.qreg[nb][kk], kk == 0 ? zero16 : s_a[nb], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) {
+                    if (kk == 0) mfma_score_init(s_a[nb], w.opreg[kk], w.qreg[nb][kk], zero16);
+                    else mfma_score(s_a[nb], w.opreg[kk], w.qreg[nb][kk]);
+                }
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) w.opreg[kk] = load_k_operand<D, NB, 1>(w.k_addr, kk);
+            settle_scores<NB>(s_a, true);
         }
         if ((i_begin + 1) * 32 > c.key_end) mask_scores<NB>(i_begin, half, c.key_end, s_a);
 #pragma unroll
@@ -685,21 +860,24 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 
         // ---- results of this segment: final rows, or (a unit shared with other workgroups)
         // running maximum, row sum and unnormalised rows into this workgroup's slot
-        static_assert(NB == 1, "store_rows handles one 32-row block per wave");
+        settle_acc<D, NB>(w.acc, false);
         const int lane = opaque(lane_id), col = lane % 32, half = lane / 32;
         const bool whole = (t_begin == 0) && (uint32_t(t_stop) == tpu);
-        const float l_tot = w.l_run[0] + other_half(w.l_run[0]);
-        const int row0 = wave * 32;
-        if (whole) {
-            const int q0 = qtile * kBM + row0;
-            store_rows<D>(out_lds, w.acc, 1.0f / l_tot, a.o + head_off + int64_t(q0) * stride_tok, stride_tok, n - q0, lane);
-        } else {
-            float *slot = a.ws + (size_t(2) * lp + (first_segment ? 0 : 1)) * slot_floats<D>();
-            if (half == 0) {
-                slot[row0 + col] = -w.neg_m[0][0];
-                slot[kBM + row0 + col] = l_tot;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const float l_tot = w.l_run[nb] + other_half(w.l_run[nb]);
+            const int row0 = wave * (32 * NB) + nb * 32;
+            if (whole) {
+                const int q0 = qtile * kBM + row0;
+                store_rows<D, NB>(out_lds, w.acc, nb, 1.0f / l_tot, a.o + head_off + int64_t(q0) * stride_tok, stride_tok, n - q0, lane);
+            } else {
+                float *slot = a.ws + (size_t(2) * lp + (first_segment ? 0 : 1)) * slot_floats<D>();
+                if (half == 0) {
+                    slot[row0 + col] = -w.neg_m[nb][0];
+                    slot[kBM + row0 + col] = l_tot;
+                }
+                store_rows<D, NB>(out_lds, w.acc, nb, 1.0f, reinterpret_cast<__bf16 *>(slot + 2 * kBM) + row0 * D, D, 32, lane);
             }
-            store_rows<D>(out_lds, w.acc, 1.0f, reinterpret_cast<__bf16 *>(slot + 2 * kBM) + row0 * D, D, 32, lane);
         }
         first_segment = false;
         if (!nxt.valid) break;
@@ -913,8 +1091,8 @@ int attention_call(const void *q, const void *k, const void *v, void *o, int32_t
     a.scale_log2e = scale * 1.4426950408889634f;
     a.n = int(n_tokens);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (head_dim == 128) return launch<128, kBlocksPerWave>(a, int(all_heads), workspace, workspace_bytes, st);
-    return launch<64, kBlocksPerWave>(a, int(all_heads), workspace, workspace_bytes, st);
+    if (head_dim == 128) return launch<128, blocks_per_wave(128)>(a, int(all_heads), workspace, workspace_bytes, st);
+    return launch<64, blocks_per_wave(64)>(a, int(all_heads), workspace, workspace_bytes, st);
 }
 
 }  // namespace
