@@ -19,6 +19,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "lp_oracle.c")
+_SRC_BLOCK = os.path.join(_HERE, "lp_block_oracle.c")
 _LIB = os.path.join(_HERE, "liblp_oracle.so")
 
 # -ffp-contract=off and no -ffast-math: the reconstruction's binary32 operation
@@ -27,11 +28,11 @@ _CFLAGS = ["-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared
 
 
 def build(force: bool = False) -> str:
-    """Compile lp_oracle.c with gcc into liblp_oracle.so (next to the source)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    """Compile lp_oracle.c and lp_block_oracle.c with gcc into liblp_oracle.so (next to the sources)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BLOCK))
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.run(["gcc", *_CFLAGS, "-o", tmp, _SRC, "-lm"], check=True)
+        subprocess.run(["gcc", *_CFLAGS, "-o", tmp, _SRC, _SRC_BLOCK, "-lm"], check=True)
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -109,6 +110,12 @@ def _load():
         lib.lpo_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                       C.c_int32, C.c_int64, C.c_int64, C.c_double, C.c_void_p, C.c_int64]
         lib.lpo_attention.restype = C.c_int
+        lib.lpo_linear.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
+        lib.lpo_linear.restype = None
+        lib.lpo_rms_norm_heads.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_double]
+        lib.lpo_rms_norm_heads.restype = None
+        lib.lpo_rope3d.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, i32p, i32p, i32p, C.c_double]
+        lib.lpo_rope3d.restype = C.c_int
         lib.lpo_num_threads.argtypes = []
         lib.lpo_num_threads.restype = C.c_int
         _lib = lib
@@ -218,3 +225,64 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, *, scale: Optional[fl
 def num_threads() -> int:
     """Threads the oracle's parallel loops use."""
     return int(_load().lpo_num_threads())
+
+
+# ---- the DiT-block operations next to attention (lp_block_oracle.c)
+
+def rope_split(head_dim: int):
+    """The split of head_dim into (temporal, height, width) parts used throughout: height and
+    width get 2 * floor(head_dim / 6) each, the temporal part the rest (128 -> 44, 42, 42)."""
+    hw = 2 * (head_dim // 6)
+    return (head_dim - 2 * hw, hw, hw)
+
+
+def linear(x: np.ndarray, w: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """y = x w^T + bias.  x: uint16 bf16 bits [n, d_in]; w: uint16 [d_out, d_in]; bias float32 [d_out] or None.
+    Returns float32 [n, d_out]."""
+    assert x.dtype == np.uint16 and w.dtype == np.uint16 and x.ndim == 2 and w.ndim == 2 and x.shape[1] == w.shape[1]
+    x, w = np.ascontiguousarray(x), np.ascontiguousarray(w)
+    n, d_in = x.shape
+    d_out = w.shape[0]
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    assert b is None or b.shape == (d_out,)
+    y = np.empty((n, d_out), dtype=np.float32)
+    _load().lpo_linear(x.ctypes.data, w.ctypes.data, None if b is None else b.ctypes.data, n, d_in, d_out, y.ctypes.data)
+    return y
+
+
+def rms_norm_heads(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """Per-(token, head) RMS normalisation over head_dim times gain[head, d].  x: float32 [n, heads, head_dim]."""
+    out = np.array(x, dtype=np.float32, order="C", copy=True)
+    n, heads, hd = out.shape
+    g = np.ascontiguousarray(gain, dtype=np.float32)
+    assert g.shape == (heads, hd)
+    _load().lpo_rms_norm_heads(out.ctypes.data, g.ctypes.data, n, heads, hd, float(eps))
+    return out
+
+
+def rope3d(x: np.ndarray, grid: Sequence[int], offset: Sequence[int] = (0, 0, 0), split: Optional[Sequence[int]] = None,
+           base: float = 10000.0) -> np.ndarray:
+    """3-D rotary encoding of x float32 [n, heads, head_dim] over the (t, h, w) patch grid `grid` (n = product)."""
+    out = np.array(x, dtype=np.float32, order="C", copy=True)
+    n, heads, hd = out.shape
+    split = rope_split(hd) if split is None else tuple(split)
+    rc = _load().lpo_rope3d(out.ctypes.data, n, heads, hd, _i32(grid), _i32(offset), _i32(split), float(base))
+    if rc != 0:
+        raise ValueError("rotary split must be even parts adding up to head_dim, and the grid must hold n tokens")
+    return out
+
+
+def qkv_block(x: np.ndarray, w_qkv: np.ndarray, bias: Optional[np.ndarray], gain_q: np.ndarray, gain_k: np.ndarray,
+              eps: float, heads: int, head_dim: int, grid: Sequence[int], offset: Sequence[int] = (0, 0, 0),
+              split: Optional[Sequence[int]] = None, base: float = 10000.0):
+    """The block's way into attention: y = x w_qkv^T + bias, cut into the q | k | v sections of d_model
+    features each ([n, heads, head_dim]); q and k are normalised per head and rotated, v is left as it is.
+    Returns (q, k, v) float32."""
+    dm = heads * head_dim
+    assert w_qkv.shape == (3 * dm, dm)
+    y = linear(x, w_qkv, bias)
+    n = y.shape[0]
+    q, k, v = (np.ascontiguousarray(y[:, s * dm:(s + 1) * dm]).reshape(n, heads, head_dim) for s in range(3))
+    q = rope3d(rms_norm_heads(q, gain_q, eps), grid, offset, split, base)
+    k = rope3d(rms_norm_heads(k, gain_k, eps), grid, offset, split, base)
+    return q, k, v
