@@ -105,6 +105,8 @@ def main() -> int:
     }
     if loop:
         result["loop"] = m["loop"]
+    if not args.guided:
+        result["block_ops"] = block_ops(ctx, run, check=not args.no_cpu_baseline)
     if not args.no_cpu_baseline and not args.guided:
         result["cpu_baseline"] = cpu_baseline(ctx, run)
     del run
@@ -383,6 +385,80 @@ def other_configs(ctx, args):
         del run
         torch.cuda.empty_cache()
     return out
+
+
+def block_ops(ctx, run, calls=5, check=True):
+    """The DiT-block operations around the attention core at the shape of the workload's largest sub-latent:
+    lp_qkv_projection (projection with q / k normalisation and rotation in its epilogue), lp_attention on what it
+    wrote, lp_linear as the output projection -- each timed alone, back to back calls between two events; a few
+    tokens of q, k, v are compared with the oracle.  (The paper fixes none of the block's internals; see lp.h.)"""
+    lp, synth, np, torch, w = ctx.lp, ctx.synth, ctx.np, ctx.torch, run.w
+    dim = sorted(run.state)[0]
+    st = run.state[dim]
+    kp = max(range(len(st["parts"])), key=lambda i: st["parts"][i].n_tokens)
+    part = st["parts"][kp]
+    n, heads, hd = int(part.n_tokens), w.heads, w.head_dim
+    dm = heads * hd
+    grid = tuple(int(part.shape[1 + d]) // w.patch[d] for d in range(3))
+    offset = [0, 0, 0]
+    offset[dim] = int(part.alpha_ext)
+    seed = synth.seed_for(run.cfg, dim, kp, tensor=30)
+
+    def bf16_dev(sub, shape, scale):
+        parts = [ctx.pool.submit(lambda r=r: synth.f32_to_bf16_bits(np.float32(scale) * synth.normal_f32(seed, (r[1] - r[0],) + shape[1:], substream=sub * 64 + i)))
+                 for i, r in enumerate(_row_chunks(shape[0], 16))]
+        host = np.concatenate([f.result() for f in parts])
+        return host, torch.from_numpy(host.view(np.int16)).cuda()
+
+    x_h, x = bf16_dev(1, (n, dm), 1.0)
+    wq_h, w_qkv = bf16_dev(2, (3 * dm, dm), dm ** -0.5)
+    _, w_o = bf16_dev(3, (dm, dm), dm ** -0.5)
+    bias_h = 0.5 * synth.normal_f32(seed, (3 * dm,), substream=250)
+    gq_h = 1.0 + 0.2 * synth.normal_f32(seed, (heads, hd), substream=251)
+    gk_h = 1.0 + 0.2 * synth.normal_f32(seed, (heads, hd), substream=252)
+    bias, gq, gk = (torch.from_numpy(a).cuda() for a in (bias_h, gq_h, gk_h))
+    q, k, v, o = (torch.empty((n, heads, hd), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+    y = torch.empty((n, dm), dtype=torch.bfloat16, device="cuda")
+    rope = lp.make_rope(grid, offset, head_dim=hd)
+    stream = ctx.stream
+    ops = {
+        "qkv_projection": (lambda: lp.lp_qkv_projection(x, w_qkv, bias, gq, gk, 1e-6, rope, q, k, v, n, heads, hd, stream), 2.0 * n * dm * 3 * dm),
+        "attention": (lambda: lp.lp_attention(q, k, v, o, n, heads, hd, heads * hd, hd, 0.0, run.ws, run.ws_bytes, stream), 4.0 * n * n * hd * heads),
+        "out_projection": (lambda: lp.lp_linear(o, w_o, bias[:dm], y, n, dm, dm, stream), 2.0 * n * dm * dm),
+    }
+    res = {"tokens": n, "heads": heads, "head_dim": hd, "d_model": dm, "patch_grid": list(grid), "grid_offset": offset}
+    total_ms = total_flops = 0.0
+    for name, (fn, flops) in ops.items():
+        fn(); fn()
+        a, b = ctx.ev(), ctx.ev()
+        a.record()
+        for _ in range(calls):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / calls
+        total_ms += ms
+        total_flops += flops
+        res[name] = {"ms": round(ms, 4), "tflops": round(flops / ms / 1e9, 1), "frac": round(flops / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    res["block_attention_path"] = {"ms": round(total_ms, 4), "tflops": round(total_flops / total_ms / 1e9, 1),
+                                   "frac": round(total_flops / total_ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    if check:
+        from oracle import lp_oracle as orc
+        rows = [0, n // 3, n - 1]
+        worst = 0.0
+        got = [t.view(torch.int16).cpu().numpy().view(np.uint16) for t in (q, k, v)]
+        for r in rows:
+            c = [r // (grid[1] * grid[2]) + offset[0], (r // grid[2]) % grid[1] + offset[1], r % grid[2] + offset[2]]
+            want = orc.qkv_block(x_h[r:r + 1], wq_h, bias_h, gq_h, gk_h, 1e-6, heads, hd, (1, 1, 1), c)
+            for g_bits, e in zip(got, want):
+                worst = max(worst, float(np.max(np.abs(synth.bf16_bits_to_f32(g_bits[r:r + 1]) - e) / (2.0 ** -8 * np.abs(e) + 3e-4))))
+        res["qkv_vs_oracle_on_3_tokens"] = {"worst_error_over_bound": round(worst, 3), "bound": "2^-8 |want| + 3e-4"}
+    return res
+
+
+def _row_chunks(rows, n):
+    step = (rows + n - 1) // n
+    return [(i, min(rows, i + step)) for i in range(0, rows, step)]
 
 
 def k1_comparison(ctx, run, calls=5):

@@ -227,6 +227,63 @@ int lp_attention_batch(const void *q, const void *k, const void *v, void *o, int
 int64_t lp_attention_workspace_size(int32_t head_dim);
 
 /*
+ * ---- The DiT-block operations on either side of the attention core -------------------------
+ * The paper says only that the denoiser is a stack of DiT blocks (Sec. 5.1) whose atomic units
+ * are the patches (Sec. 3.1); it fixes none of the block's internals.  The form taken here is
+ * the common one and is this library's stated reading, not the paper's:
+ *   y = x W^T + b,  cut into q | k | v sections of d_model = heads * head_dim features each;
+ *   q, k <- x / sqrt(mean_d x^2 + eps) * gain[head, d]   per (token, head), over head_dim;
+ *   q, k <- rotated pairwise: elements (2 j, 2 j + 1) of a part of size p of head_dim turn by
+ *           pos * base^(-2 j / p), the three parts split[0..2] (even, adding up to head_dim)
+ *           taking pos = the token's t, h, w patch coordinate in turn;
+ *   out = o W_o^T + b_o after attention.
+ * Tokens are the patches of the sub-latent in row-major (t, h, w) order (grid[0..2], whose
+ * product is n_tokens); offset[0..2] is added to the coordinates (0 = coordinates local to
+ * the sub-latent; alpha'_k along the partition dimension places it in the global grid).
+ */
+typedef struct lp_rope {
+    int32_t grid[3];   /* patches of the sub-latent along T, H, W                      */
+    int32_t offset[3]; /* added to the patch coordinates                               */
+    int32_t split[3];  /* head_dim features rotated by t, h, w: even, sum = head_dim   */
+    float base;        /* > 0, e.g. 10000                                              */
+} lp_rope;
+
+/*
+ * q | k | v = x w_qkv^T + bias with the normalisation and rotation of q and k done in the
+ * product's epilogue (one launch; q, k, v are written once, in the layout lp_attention reads).
+ * x: device, bf16 [n_tokens, d_model].  w_qkv: device, bf16 [3 d_model, d_model], row o holding
+ * the weights of output feature o; rows [0, d_model) produce q, [d_model, 2 d_model) k, the rest v.
+ * bias: device, binary32 [3 d_model], or NULL.  gain_q, gain_k: device, binary32 [heads, head_dim].
+ * q, k, v: device, bf16 [n_tokens, heads, head_dim] contiguous, fully overwritten; they must not
+ * alias each other or x.  All pointers 16-byte aligned.  rope: host pointer.
+ * head_dim in {64, 128}, d_model a multiple of 128 (else LP_ERR_UNSUPPORTED); n_tokens = 0 is a
+ * successful no-op.  The product runs on bf16 MFMA with binary32 accumulation; bias, normalisation
+ * and rotation are binary32 (angles via the hardware sine / cosine of the fractional turn count);
+ * the result is rounded to bf16 once, on store.
+ */
+int lp_qkv_projection(const void *x, const void *w_qkv, const float *bias, const float *gain_q, const float *gain_k,
+                      float eps, const lp_rope *rope, void *q, void *k, void *v, int64_t n_tokens, int32_t heads,
+                      int32_t head_dim, void *stream);
+
+/*
+ * y = x w^T + bias: the block's output projection (or any linear layer of these shapes).
+ * x: device, bf16 [n, d_in]; w: device, bf16 [d_out, d_in]; bias: device, binary32 [d_out] or NULL;
+ * y: device, bf16 [n, d_out], fully overwritten, must not alias x or w.  d_in a multiple of 64,
+ * d_out a multiple of 128 (else LP_ERR_UNSUPPORTED).  bf16 MFMA, binary32 accumulation, one
+ * rounding to bf16 on store.
+ */
+int lp_linear(const void *x, const void *w, const float *bias, void *y, int64_t n, int32_t d_in, int32_t d_out,
+              void *stream);
+
+/*
+ * The normalisation + rotation of lp_qkv_projection alone, in place, for q or k projected
+ * elsewhere.  x: device, bf16, element (token, head, d) at token * stride_tok + head * stride_head
+ * + d (strides as in lp_attention).  gain: device, binary32 [heads, head_dim].
+ */
+int lp_qk_norm_rope(void *x, const float *gain, float eps, const lp_rope *rope, int64_t n_tokens, int32_t heads,
+                    int32_t head_dim, int64_t stride_tok, int64_t stride_head, void *stream);
+
+/*
  * lp_attention for callers that cannot allocate device memory or hand over a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
  * the same kernels, with the scratch for shared query tiles taken from a fixed array that

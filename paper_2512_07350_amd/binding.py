@@ -34,7 +34,8 @@ EXPORTS = (
     "lp_plan_total_elems", "lp_plan_latent_elems", "lp_plan_query", "lp_partition", "lp_reconstruct",
     "lp_reconstruct_guided_step", "lp_reconstruct_guided_step_partition",
     "lp_attention", "lp_attention_batch", "lp_attention_workspace_size", "lp_attention_static",
-    "lp_attention_static_scratch_bytes", "lp_strerror", "lp_last_hip_error", "lp_version",
+    "lp_attention_static_scratch_bytes", "lp_qkv_projection", "lp_linear", "lp_qk_norm_rope",
+    "lp_strerror", "lp_last_hip_error", "lp_version",
 )
 
 
@@ -49,6 +50,10 @@ class lp_part_info(C.Structure):
                 ("s", C.c_int32), ("e", C.c_int32), ("len", C.c_int32),
                 ("delta_start", C.c_int32), ("delta_end", C.c_int32), ("shape", C.c_int32 * 4),
                 ("elem_offset", C.c_int64), ("n_elems", C.c_int64), ("n_tokens", C.c_int64)]
+
+
+class lp_rope(C.Structure):
+    _fields_ = [("grid", C.c_int32 * 3), ("offset", C.c_int32 * 3), ("split", C.c_int32 * 3), ("base", C.c_float)]
 
 
 class LPError(RuntimeError):
@@ -108,6 +113,12 @@ def _lib():
         lib.lp_attention_static.restype = C.c_int
         lib.lp_attention_static_scratch_bytes.argtypes = []
         lib.lp_attention_static_scratch_bytes.restype = i64
+        lib.lp_qkv_projection.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.POINTER(lp_rope), vp, vp, vp, i64, i32, i32, vp]
+        lib.lp_qkv_projection.restype = C.c_int
+        lib.lp_linear.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp]
+        lib.lp_linear.restype = C.c_int
+        lib.lp_qk_norm_rope.argtypes = [vp, vp, C.c_float, C.POINTER(lp_rope), i64, i32, i32, i64, i64, vp]
+        lib.lp_qk_norm_rope.restype = C.c_int
         lib.lp_attention_workspace_size.argtypes = [i32]
         lib.lp_attention_workspace_size.restype = i64
         lib.lp_strerror.argtypes = [C.c_int]
@@ -272,3 +283,33 @@ def lp_attention_static(q, k, v, o, n_tokens: int, heads: int, head_dim: int, st
 
 def lp_attention_static_scratch_bytes() -> int:
     return int(_lib().lp_attention_static_scratch_bytes())
+
+
+def make_rope(grid, offset=(0, 0, 0), split=None, base: float = 10000.0, head_dim: int = 128) -> lp_rope:
+    """The rotary description; split defaults to (head_dim - 4 floor(head_dim / 6), 2 floor(head_dim / 6), 2 floor(head_dim / 6))."""
+    if split is None:
+        hw = 2 * (head_dim // 6)
+        split = (head_dim - 2 * hw, hw, hw)
+    r = lp_rope()
+    for i in range(3):
+        r.grid[i], r.offset[i], r.split[i] = int(grid[i]), int(offset[i]), int(split[i])
+    r.base = float(base)
+    return r
+
+
+def lp_qkv_projection(x, w_qkv, bias, gain_q, gain_k, eps: float, rope: lp_rope, q, k, v, n_tokens: int, heads: int,
+                      head_dim: int, stream: Optional[int] = None) -> None:
+    _check(_lib().lp_qkv_projection(_ptr(x), _ptr(w_qkv), _ptr(bias) or None, _ptr(gain_q), _ptr(gain_k), float(eps),
+                                    C.byref(rope), _ptr(q), _ptr(k), _ptr(v), int(n_tokens), int(heads), int(head_dim),
+                                    stream or None), "lp_qkv_projection")
+
+
+def lp_linear(x, w, bias, y, n: int, d_in: int, d_out: int, stream: Optional[int] = None) -> None:
+    _check(_lib().lp_linear(_ptr(x), _ptr(w), _ptr(bias) or None, _ptr(y), int(n), int(d_in), int(d_out), stream or None),
+           "lp_linear")
+
+
+def lp_qk_norm_rope(x, gain, eps: float, rope: lp_rope, n_tokens: int, heads: int, head_dim: int, stride_tok: int,
+                    stride_head: int, stream: Optional[int] = None) -> None:
+    _check(_lib().lp_qk_norm_rope(_ptr(x), _ptr(gain), float(eps), C.byref(rope), int(n_tokens), int(heads), int(head_dim),
+                                  int(stride_tok), int(stride_head), stream or None), "lp_qk_norm_rope")

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "liblp_mi355x.so")
 
-SOURCES = ["lp_plan.cpp", "lp_latent.hip", "lp_attention.hip"]
+SOURCES = ["lp_plan.cpp", "lp_latent.hip", "lp_attention.hip", "lp_block.hip"]
 
 # Packed-FP32 instructions are kept off for every device translation unit.
 HOST = ["-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC, "-Wall", "-Wno-unused-function"]

@@ -144,3 +144,17 @@ def test_device_calls_reject_bad_arguments_without_a_gpu():
     assert lib.lp_attention_batch(16, 32, 48, 64, 2, 10, 4, 64, 1280, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention_batch(16, 32, 48, 64, 2, 10, 4, 64, 2564, 256, 64, 0.0, None, 0, None) == lp.LP_ERR_INVALID_ARG
     assert lib.lp_attention_batch(None, None, None, None, 2, 0, 4, 64, 2560, 256, 64, 0.0, None, 0, None) == lp.LP_OK
+
+
+def test_block_calls_reject_bad_arguments_without_a_gpu():
+    lib = lp._lib()
+    rope = lp.make_rope((1, 1, 4), head_dim=128)
+    assert lib.lp_linear(16, 32, None, 48, 4, 100, 128, None) == lp.LP_ERR_UNSUPPORTED        # d_in not a multiple of 64
+    assert lib.lp_linear(16, 32, None, 48, 4, 128, 100, None) == lp.LP_ERR_UNSUPPORTED        # d_out not a multiple of 128
+    assert lib.lp_linear(16, 32, None, 16, 4, 128, 128, None) == lp.LP_ERR_INVALID_ARG        # y is x
+    assert lib.lp_linear(None, None, None, None, 0, 128, 128, None) == lp.LP_OK
+    assert lib.lp_qkv_projection(16, 32, None, 48, 64, 1e-6, C.byref(rope), 80, 96, 112, 4, 1, 96, None) == lp.LP_ERR_UNSUPPORTED
+    assert lib.lp_qkv_projection(16, 32, None, 48, 64, 1e-6, C.byref(rope), 80, 96, 112, 5, 1, 128, None) == lp.LP_ERR_INVALID_ARG  # grid holds 4 tokens
+    bad = lp.make_rope((1, 1, 4), split=(43, 43, 42), head_dim=128)
+    assert lib.lp_qkv_projection(16, 32, None, 48, 64, 1e-6, C.byref(bad), 80, 96, 112, 4, 1, 128, None) == lp.LP_ERR_INVALID_ARG   # odd parts
+    assert lib.lp_qk_norm_rope(16, 32, 1e-6, C.byref(rope), 4, 1, 128, 128, 100, None) == lp.LP_ERR_INVALID_ARG                     # stride_head < head_dim
