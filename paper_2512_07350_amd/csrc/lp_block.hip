@@ -47,6 +47,7 @@ constexpr int kStageBytes = 2 * kTileBytes;      // W tile then x tile
 constexpr int kStagesG = 2;
 constexpr int kLdsBytes = kStagesG * kStageBytes;
 constexpr int kThreadsG = 512;
+constexpr int kPanel = 4;                // token tiles per panel of the tile order
 constexpr int kMaxPairs = 64;            // rotary pairs per head (head_dim <= 128)
 
 // floor(n / d) for 0 <= n < 2^31 as (n * magic) >> shift (64-bit product); see make_fastdiv.
@@ -84,7 +85,7 @@ struct GemmArgs {
     const float *gain[2];        // qkv: gain_q, gain_k [heads, head_dim]
     int32_t n, d_in, d_out;
     int32_t heads;               // qkv: heads; d_out = 3 * heads * head_dim
-    int32_t n_ftiles;
+    int32_t n_ftiles, n_ttiles;
     RopeArgs rope;
 };
 
@@ -124,6 +125,21 @@ __device__ __forceinline__ uint32_t logical_workgroup(uint32_t b, uint32_t n_wg)
     const uint32_t xcd = b % 8, slot = b / 8;
     const uint32_t base = n_wg / 8, rem = n_wg % 8;
     return xcd * base + (xcd < rem ? xcd : rem) + slot;
+}
+
+// One matrix instruction, acc += a . b, as an assembly statement: such statements keep their
+// program order, and the LDS reads written between them stay between them.  The compiler does
+// not know what the statement is and adds no wait states after it: settle() stands between the
+// last product and the first vector instruction that reads an accumulator.
+__device__ __forceinline__ void mfma(f32x16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void settle(f32x16 (&acc)[4][2]) {
+    asm volatile("s_nop 15\n\ts_nop 7");
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) asm volatile("" : "+v"(acc[mb][nb]));
 }
 
 // Writes 32 result rows (tokens) of 128 features, rounded to bf16, to dst + r * row_stride
@@ -213,8 +229,14 @@ __global__ __launch_bounds__(kThreadsG) void gemm_kernel(const GemmArgs a) {
     const int lane = tid % 64, col = lane % 32, half = lane / 32;
     const int fw = wave / 4, tq = wave % 4;              // feature half, token quarter of the workgroup tile
 
+    // Tiles are ordered in panels of kPanel token tiles, feature tile by feature tile inside a
+    // panel: the 32 workgroups an XCD runs at a time then cover 8 feature tiles x 4 token tiles
+    // and share their W and x rows through its L2 (12 operand tiles fetched for 32 products).
     const uint32_t lw = logical_workgroup(blockIdx.x, gridDim.x);
-    const int ttile = int(lw) / a.n_ftiles, ftile = int(lw) % a.n_ftiles;
+    const int panel_tiles = kPanel * a.n_ftiles;
+    const int panel = int(lw) / panel_tiles, in_panel = int(lw) - panel * panel_tiles;
+    const int panel_h = min(kPanel, a.n_ttiles - panel * kPanel);
+    const int ftile = in_panel / panel_h, ttile = panel * kPanel + in_panel - ftile * panel_h;
     const int f0 = ftile * kTF, t0 = ttile * kTT;
 
     // raw buffers over the rows this tile can touch (rows past the end read as zeros)
@@ -271,21 +293,32 @@ __global__ __launch_bounds__(kThreadsG) void gemm_kernel(const GemmArgs a) {
         wait_all_tile_loads();
         __syncthreads();          // stage kt has landed for everyone; everyone has left the other stage
         if (kt + 1 < n_kt) issue(kt + 1, kStageBytes - stage);
+        // Operands of k-step s+1 are fetched from LDS while the products of step s run: two
+        // register sets, one fetch after each of the first six products of a step.  The products
+        // are assembly statements so that this order stands (left to the scheduler, an operand is
+        // fetched right before its two products and the wave sits out the LDS latency every time);
+        // LDS reads keep their place between such statements.
+        // granule (2 s + half) ^ swz(row) = (half ^ swz(row)) ^ (2 s): a step flips bits 1-2 of the granule index
+        bf16x8 aop[2][4], bop[2][2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) bop[0][nb] = lds_load<bf16x8>(b_addr[nb] + stage);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) aop[0][mb] = lds_load<bf16x8>(a_addr[mb] + stage);
 #pragma unroll
         for (int s = 0; s < kBK / 16; ++s) {
-            // granule (2 s + half) ^ swz(row) = (half ^ swz(row)) ^ (2 s): the step flips bits 1-2 of the granule index
-            bf16x8 aop[4], bop[2];
+            const int cur = s & 1, nxt = cur ^ 1;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) aop[mb] = lds_load<bf16x8>((a_addr[mb] + stage) ^ uint32_t(32 * s));
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) bop[nb] = lds_load<bf16x8>((b_addr[nb] + stage) ^ uint32_t(32 * s));
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[mb], bop[nb], acc[mb][nb], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) {
+                const int mb = i / 2, nb = i % 2;
+                mfma(acc[mb][nb], aop[cur][mb], bop[cur][nb]);
+                if (s + 1 < kBK / 16) {
+                    if (i < 2) bop[nxt][i] = lds_load<bf16x8>((b_addr[i] + stage) ^ uint32_t(32 * (s + 1)));
+                    else if (i < 6) aop[nxt][i - 2] = lds_load<bf16x8>((a_addr[i - 2] + stage) ^ uint32_t(32 * (s + 1)));
+                }
+            }
         }
     }
+    settle(acc);
 
     // ---- epilogue; the tile ring is free once every wave has left it
     __syncthreads();
@@ -448,7 +481,8 @@ int launch_gemm(GemmArgs a, hipStream_t stream) {
         attr_set.fetch_or(dev_bit, std::memory_order_relaxed);
     }
     a.n_ftiles = (a.d_out + kTF - 1) / kTF;
-    const int64_t tiles = int64_t(a.n_ftiles) * ((a.n + kTT - 1) / kTT);
+    a.n_ttiles = int32_t((a.n + kTT - 1) / kTT);
+    const int64_t tiles = int64_t(a.n_ftiles) * a.n_ttiles;
     if (tiles >= (int64_t(1) << 31)) return LP_ERR_UNSUPPORTED;
     return lp::launch_kernel(kern, dim3(uint32_t(tiles)), dim3(kThreadsG), kLdsBytes, stream, a);
 }

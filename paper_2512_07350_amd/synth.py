@@ -53,6 +53,8 @@ WORKLOADS = (
     Workload("wan1.3b-81f-480p-K2", (16, 21, 60, 104), (1, 2, 2), 2, 2, (0, 1, 2), 12, 128),
     Workload("wan1.3b-81f-480p-K8", (16, 21, 60, 104), (1, 2, 2), 8, 2, (0, 1, 2), 12, 128),
     Workload("wan1.3b-81f-480p-temporal-only", (16, 21, 60, 104), (1, 2, 2), 4, 2, (0,), 12, 128),
+    # the longest clip of the paper's duration sweep: 10 s at 16 frames per second = 161 frames = 41 latent frames
+    Workload("wan1.3b-161f-480p-r0.5", (16, 41, 60, 104), (1, 2, 2), 4, -1, (0, 1, 2), 12, 128, overlap_ratio=0.5),
 )
 
 

@@ -176,10 +176,11 @@ def test_full_size_partitions_sampled_rows(cfg, dim):
             _check_partition_sampled(cfg, dim, kp, part.n_tokens, w, seed=kp + 10 * dim)
 
 
-@pytest.mark.parametrize("cfg", [7, 8, 9])
-def test_device_count_sweep_and_temporal_only_shapes_sampled_rows(cfg):
-    """81 frames with K = 2, K = 8 and the temporal-only variant: along every dimension the
-    workload visits, its largest sub-latent and its last non-empty one (the odd-sized one)."""
+@pytest.mark.parametrize("cfg", [7, 8, 9, 10])
+def test_device_count_sweep_temporal_only_and_long_clip_shapes_sampled_rows(cfg):
+    """81 frames with K = 2, K = 8 and the temporal-only variant, and the 10-second clip (161
+    frames, r = 0.5, sub-latents of up to 34112 tokens): along every dimension the workload
+    visits, its largest sub-latent and its last non-empty one (the odd-sized one)."""
     w = synth.WORKLOADS[cfg]
     for dim in sorted(set(w.dims)):
         pl = orc.plan(w.latent, w.patch, w.K, dim, **w.overlap_args())

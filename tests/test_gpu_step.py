@@ -28,10 +28,10 @@ def test_tiny_step_end_to_end():
     assert got.tobytes() == orc.reconstruct(ref_plan, preds).tobytes()
 
 
-@pytest.mark.parametrize("cfg", [5, 6])
+@pytest.mark.parametrize("cfg", [5, 6, 10])
 def test_ratio_overlap_workloads_step(cfg):
     """49 frames at 480p, K = 4, overlap given as the ratio r (0.5: pairwise overlaps; 1.0: three
-    partitions meet): latent ops bit-exact on all three dims, the guided step too, and attention
+    partitions meet), and the 161-frame clip at r = 0.5: latent ops bit-exact on all three dims, the guided step too, and attention
     on the largest sub-latent of the H step on sampled rows."""
     from tests import gpu_util as g
     w = synth.WORKLOADS[cfg]
