@@ -118,6 +118,31 @@ def test_qkv_projection_at_benchmark_size_sampled_tokens():
             _close(a[r:r + 1], e, "%s token %d" % (name, r))
 
 
+def test_block_at_headline_size_sampled_tokens():
+    """The 40-head block (d_model 5120) over the headline workload's largest sub-latent (13230 tokens):
+    QKV projection with normalisation and rotation, then the output projection of a seeded o, each on
+    96 sampled tokens (every 256-token tile edge among the first and last tiles, plus random ones)."""
+    heads, hd, grid = 40, 128, (21, 45, 14)
+    dm, n = heads * hd, 21 * 45 * 14
+    x = _bits(911, (n, dm))
+    w = _bits(912, (3 * dm, dm), scale=dm ** -0.5)
+    b = 0.5 * synth.normal_f32(913, (3 * dm,))
+    gq = 1.0 + 0.2 * synth.normal_f32(914, (heads, hd))
+    gk = 1.0 + 0.2 * synth.normal_f32(915, (heads, hd))
+    got = _qkv(x, w, b, gq, gk, 1e-6, heads, hd, grid, (0, 0, 8), None, 10000.0)
+    assert all(np.all(np.isfinite(a)) for a in got)
+    rows = synth.sample_rows(n, 96, seed=19, tile=256)
+    for r in rows:
+        t, h, wv = r // (45 * 14), (r // 14) % 45, r % 14
+        want = orc.qkv_block(x[r:r + 1], w, b, gq, gk, 1e-6, heads, hd, (1, 1, 1), (t, h, wv + 8), None, 10000.0)
+        for name, a, e in zip("qkv", got, want):
+            _close(a[r:r + 1], e, "%s token %d" % (name, r))
+    w_o = w[:dm]
+    y = _linear(x, w_o, b[:dm])
+    assert np.all(np.isfinite(y))
+    _close(y[rows], orc.linear(x[rows], w_o, b[:dm]), "output projection, sampled tokens")
+
+
 @pytest.mark.parametrize("hd", [64, 128])
 def test_qk_norm_rope_in_place_with_padded_strides(hd):
     import torch
