@@ -164,6 +164,7 @@ struct Lane {
     uint32_t k_voff[kLd], v_voff[kLd];       // byte offset of this lane's 16 bytes in tile 0
     uint32_t ld_dst[kLd];                    // LDS offset of the 1024-byte block inside a K tile (wave-uniform)
     uint32_t tile_bytes;                     // global byte distance between consecutive tiles
+    uint32_t valid_bytes;                    // size of the K (and V) buffer of the current head: a load at or past it reads zeros and fetches nothing
     int half;                                // lane / 32
     int key_end;                             // keys at and past this index do not exist for the current segment
     int t_end;                               // one past the segment's last tile
@@ -203,6 +204,15 @@ __device__ __forceinline__ void issue_tile(uint32_t lds0, const Lane<D, NB> &c, 
         const uint32_t dst_k = __builtin_amdgcn_readfirstlane(lds0 + stage_off + c.ld_dst[i]);
         load_kv_to_lds_16<T::kTileBytes>(c.k_rsrc, c.v_rsrc, dst_k, c.k_voff[i], c.v_voff[i], soff);
     }
+}
+
+// The I-th of a wave's kLd load statements of a tile (K block and V block), at scalar byte offset
+// soff (which takes part in the buffer's range check, like the lane's own offset).
+template <int D, int NB, int I>
+__device__ __forceinline__ void issue_tile_part(uint32_t lds0, const Lane<D, NB> &c, uint32_t soff, uint32_t stage_off) {
+    using T = Tile<D, NB>;
+    const uint32_t dst_k = __builtin_amdgcn_readfirstlane(lds0 + stage_off + c.ld_dst[I]);
+    load_kv_to_lds_16<T::kTileBytes>(c.k_rsrc, c.v_rsrc, dst_k, c.k_voff[I], c.v_voff[I], soff);
 }
 
 // Keys past the end get score -inf.  Accumulator register i of a lane is key
@@ -293,7 +303,7 @@ __device__ __forceinline__ void raise_maximum(const float (&lane_max)[NB], f32x1
     bool raise = false;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) raise = raise || (lane_max[nb] > kRescaleThreshold);
-    if (__any(raise)) {
+    if (__builtin_expect(__any(raise) != 0, 0)) {     // the branch body is laid out away from the loop
         settle_acc<D, NB>(acc, false);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -432,9 +442,9 @@ __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
 //          registers it has just read, each PV group by the fetch of a K operand of round i+2
 // so that an LDS operand is fetched half a step before its products, and K and V operands
 // share one set of registers.
-// Even steps open tile t+1 (t = i/2): they wait for its loads, pass the barrier (after which
-// every wave has fetched its last operand from tile t-2), and refill that stage with tile
-// t+kStages-2.
+// Even steps open tile t+1 (t = i/2): at the end of their score phase they wait for its loads
+// and pass the barrier (after which every wave has fetched its last operand from tile t-2), and
+// over their PV phase they refill that stage with tile t+kStages-2.
 // The same code runs at the ends of a segment: with MASK, keys past the segment's end get
 // scores -inf (probabilities 0), and the round before the first has probabilities 0, so
 // the products issued for rounds that do not exist add nothing; their operands are read
@@ -446,26 +456,31 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
                                               bf16x8 (&p_prev)[NB][2], bf16x8 (&p_cur)[NB][2]) {
     using T = Tile<D, NB>;
     constexpr int KS = D / 16, MB = D / 32;
+    // Per-tile bookkeeping is scalar and happens here; what it decides is carried out inside the
+    // windows below, so that no stretch of the step is without a product to issue:
+    //  * SUB == 0 opens tile t+1 (t = i/2).  Its K operands are first fetched in the PV phase, so
+    //    the wait for its loads and the barrier (after which every wave has fetched its last
+    //    operand from tile t-2) stand at the end of the score phase; each K operand address moves
+    //    to the new stage right before its first fetch there; and the kLd load statements that
+    //    refill tile t-2's stage with tile t+kStages-2 are spread over the PV phase.  Past the
+    //    segment's end the loads are given an offset outside the buffer: they fetch nothing.
+    //  * SUB == 1: round i-1 is the first of tile i/2, the V fetches move on to that tile --
+    //    unless it lies past the segment and was never loaded (its probabilities are 0, and 0
+    //    times whatever an unwritten stage holds need not be 0); each V operand address moves
+    //    right before its first fetch of the step.
+    uint32_t k_delta = 0, v_delta = 0, issue_soff = 0, issue_stage = 0;
     if (SUB == 0) {
         if (!first) w.tile_off = next_stage<T::kStageBytes>(w.tile_off);
-        wait_tile_loads<0>();              // tile t+1, issued one tile ago
-        __syncthreads();
-        if (w.issue_t < c.t_end) issue_tile<D, NB>(lds0, c, w.issue_t, w.issue_off);
+        const uint32_t nxt_off = next_stage<T::kStageBytes>(w.tile_off);
+        k_delta = nxt_off - w.k_off;       // wraps; the sums do not
+        w.k_off = nxt_off;
+        issue_soff = w.issue_t < c.t_end ? uint32_t(w.issue_t) * c.tile_bytes : c.valid_bytes;
+        issue_stage = w.issue_off;
         ++w.issue_t;
         w.issue_off = next_stage<T::kStageBytes>(w.issue_off);
-        const uint32_t nxt_off = next_stage<T::kStageBytes>(w.tile_off);
-        const uint32_t delta = nxt_off - w.k_off;       // wraps; the sum below does not
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) w.k_addr[kk] += delta;
-        w.k_off = nxt_off;
     } else {
-        // round i-1 is the first of tile i/2: the V fetches move on to that tile -- unless it
-        // lies past the segment and was never loaded (its probabilities are 0, and 0 times
-        // whatever an unwritten stage holds need not be 0)
         if (i / 2 < c.t_end) {
-            const uint32_t delta = w.tile_off - w.v_off;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) w.v_addr[mb] += delta;
+            v_delta = w.tile_off - w.v_off;
             w.v_off = w.tile_off;
         }
     }
@@ -476,12 +491,15 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
     // one before: the vector and LDS work of the step is therefore cut into one window per
     // product -- the exponentials of round i (8 / KS per window), a conversion and a row-sum
     // update for every second of them, the refill of the operand registers the group has just
-    // read (half a V^T operand or one K operand per window), and, over the last KS/2 groups,
-    // the per-lane maximum of round i+1's scores, whose products have long left the pipeline.
+    // read (half a V^T operand or one K operand per window), in even steps a quarter of the next
+    // tile's loads in every second PV group, and, from four windows after the last score product
+    // to the end of the step, the per-lane maximum of round i+1's scores.
     static_assert(NB == 2, "the windows below are laid out for two 32-row blocks per wavefront");
     constexpr int M = 2 * KS * NB;              // products per step
     constexpr int X = (NB * 16) / M;            // exponentials per window
-    constexpr int kMaxFrom = (KS + KS / 2) * NB, kMaxPer = 16 / (KS / 2);
+    // the maximum of round i+1's scores: from four windows after its last product (whose result
+    // has then left the pipeline) to the end of the step, both blocks in turn
+    constexpr int kMaxFrom = KS * NB + 4, kMaxWin = (M - kMaxFrom) / NB;   // windows per block
     uint32_t pw[NB][2][4];
     float ex[NB * 16];
     float lane_max[NB];
@@ -500,6 +518,7 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
         if constexpr (g < KS) {
             if constexpr (g == 0) mfma_score_init(s_nxt[nb], w.opreg[g], w.qreg[nb][g], w.neg_m[nb]);
             else mfma_score(s_nxt[nb], w.opreg[g], w.qreg[nb][g]);
+            if constexpr (SUB == 1 && nb == 0 && g < MB) w.v_addr[g] += v_delta;
             if constexpr (nb == 0) vop.h[0] = load_v_half<D, NB, 1 - SUB, 0>(w.v_addr, g);
             else {
                 vop.h[1] = load_v_half<D, NB, 1 - SUB, 1>(w.v_addr, g);
@@ -508,7 +527,18 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
         } else {
             constexpr int j = g - KS;
             mfma_pv(w.acc[j % MB][nb], w.opreg[j], p_prev[nb][j / MB]);
-            if constexpr (nb == NB - 1) w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
+            if constexpr (nb == NB - 1) {
+                if constexpr (SUB == 0) w.k_addr[j] += k_delta;
+                w.opreg[j] = load_k_operand<D, NB, SUB>(w.k_addr, j);
+            } else if constexpr (SUB == 0 && nb == 0) {
+                // the tile's load statements, evenly over the PV groups
+                constexpr int kLd = Lane<D, NB>::kLd, every = KS / kLd;
+                if constexpr (j % every == 0) issue_tile_part<D, NB, j / every>(lds0, c, issue_soff, issue_stage);
+            }
+        }
+        if constexpr (SUB == 0 && m == KS * NB - 1) {
+            wait_tile_loads<0>();              // tile t+1, issued one tile ago
+            __syncthreads();
         }
         // exponentials x = m X .. of the round's NB * 16 scores.  A pair is converted in the
         // window after its second exponential (a conversion must not directly follow the
@@ -526,12 +556,12 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
             if (MASK) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
         }
         if constexpr (m >= kMaxFrom) {
-            constexpr int wdx = m - kMaxFrom, nbm = wdx % NB, first = (wdx / NB) * kMaxPer;
+            constexpr int wdx = m - kMaxFrom, nbm = wdx % NB, first = (16 * (wdx / NB)) / kMaxWin;
             // three-operand maxima, written out so that no operand is first passed through a
             // quieting v_max (the scores come from assembly statements, so the compiler cannot
             // tell that they are ordinary numbers)
             float mx = first == 0 ? s_nxt[nbm][0] : lane_max[nbm];
-            constexpr int lo = first == 0 ? 1 : first, hi = first + kMaxPer;
+            constexpr int lo = first == 0 ? 1 : first, hi = (16 * (wdx / NB + 1)) / kMaxWin;
             static_for<0, (hi - lo) / 2>([&](auto rc) {
                 constexpr int r = lo + 2 * decltype(rc)::value;
                 mx = max3(mx, s_nxt[nbm][r], s_nxt[nbm][r + 1]);
@@ -654,6 +684,7 @@ __device__ __forceinline__ void start_tiles(uint32_t lds0, const AttnParams &a, 
         // raw buffers over this head's K and V, ending with the last element of token n-1
         // (flags: 32-bit data format, as every untyped buffer on this architecture)
         const int valid_bytes = int((int64_t(n - 1) * stride_tok + D) * 2);
+        c.valid_bytes = uint32_t(valid_bytes);
         const __bf16 *kh = a.k + head_off, *vh = a.v + head_off;
         c.k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(kh), 0, valid_bytes, 0x00020000);
         c.v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(vh), 0, valid_bytes, 0x00020000);
