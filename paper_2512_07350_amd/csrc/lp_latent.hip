@@ -293,6 +293,71 @@ __global__ __launch_bounds__(kThreads) void reconstruct_kernel(const float *__re
     }
 }
 
+// ---- Partition along the fastest dimension (inner == 1), four floats per vector.
+// A sub-latent's row is then a run of only len_k floats (96-112 bytes on the 720p latent): lanes
+// that write one side contiguously touch two or three partial 128-byte lines per run on the other
+// side, and partition_kernel spends its time in the address path, not on bandwidth.  The kernel
+// below takes R consecutive rows per workgroup and passes them through LDS: the R rows of the
+// latent are one contiguous block, and so are the R rows of every sub-latent (rows are packed back
+// to back), so every global access is a contiguous stream of whole lines, and the short runs are
+// taken apart in LDS.  (The same staging for lp_reconstruct was built and measured slower than
+// reconstruct_kernel, 21-26 us against 14.6 us on the 19.4 MB latent, and is not kept.)
+constexpr uint32_t kRowsLdsBytes = 32768;   // LDS per workgroup for the rows held by the kernel below
+
+struct RowsArgs {
+    int32_t s[LP_MAX_PARTS];            // Eq. 9
+    int32_t len[LP_MAX_PARTS];          // l_k
+    uint32_t off[LP_MAX_PARTS];         // first float4 of sub-latent k in the packed buffer
+    FastDiv len4[LP_MAX_PARTS];         // len_k / 4
+    int32_t K;
+    uint32_t rows;                      // outer
+    uint32_t R;                         // rows per workgroup
+    uint32_t w4;                        // extent / 4
+};
+
+// Eq. 10: LDS holds the R latent rows; sub-latent k's R rows leave as one contiguous block.
+__global__ __launch_bounds__(kThreads) void partition_rows_kernel(const float4 *__restrict__ z, float4 *__restrict__ subs,
+                                                                  const RowsArgs a) {
+    extern __shared__ float4 rows_lds[];
+    const uint32_t o0 = blockIdx.x * a.R;
+    const uint32_t rows = min(a.R, a.rows - o0);
+    const float4 *src = z + uint64_t(o0) * a.w4;
+    for (uint32_t i = threadIdx.x; i < rows * a.w4; i += kThreads) rows_lds[i] = src[i];
+    __syncthreads();
+    for (int k = 0; k < a.K; ++k) {
+        const uint32_t l4 = a.len4[k].d;
+        if (a.len[k] == 0) continue;
+        float4 *dst = subs + a.off[k] + uint64_t(o0) * l4;
+        const uint32_t s4 = uint32_t(a.s[k]) / 4;
+        for (uint32_t i = threadIdx.x; i < rows * l4; i += kThreads) {
+            const uint32_t r = fastdiv(i, a.len4[k]);
+            dst[i] = rows_lds[r * a.w4 + s4 + (i - r * l4)];
+        }
+    }
+}
+
+// Fills the arguments of partition_rows_kernel; false if this plan is not for it (the partition
+// dimension is not the fastest one, vectors of four do not fit, or a latent row exceeds the LDS share).
+bool make_rows_args(const lp_plan *pl, RowsArgs *a) {
+    if (pl->inner != 1 || pl->extent % 4 != 0) return false;
+    a->K = pl->K;
+    for (int k = 0; k < pl->K; ++k) {
+        const lp_part_info &q = pl->part[k];
+        if (q.len % 4 != 0 || q.s % 4 != 0 || q.elem_offset % 4 != 0) return false;
+        a->s[k] = q.s;
+        a->len[k] = q.len;
+        a->off[k] = uint32_t(q.elem_offset / 4);
+        a->len4[k] = make_fastdiv(q.len ? uint32_t(q.len / 4) : 1);
+    }
+    const uint32_t w4 = uint32_t(pl->extent / 4);
+    if (w4 * 16 > kRowsLdsBytes) return false;
+    const uint32_t R = kRowsLdsBytes / (w4 * 16);
+    a->rows = uint32_t(pl->latent_elems / pl->extent);
+    a->R = R > 32 ? 32 : R;
+    a->w4 = w4;
+    return true;
+}
+
 bool aligned_to(const void *p, int bytes) { return (reinterpret_cast<uintptr_t>(p) % bytes) == 0; }
 
 // Widest vector usable for this plan and these pointers.  Either the vector lies
@@ -394,7 +459,13 @@ int lp_partition(const lp_plan *plan, const float *z, float *subs_packed, void *
     if (!aligned_to(z, 4) || !aligned_to(subs_packed, 4) || z == subs_packed) return LP_ERR_INVALID_ARG;
     if (!fits_32bit(plan)) return LP_ERR_UNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    switch (pick_vec(plan, z, subs_packed)) {
+    const int vec = pick_vec(plan, z, subs_packed);
+    RowsArgs rows;
+    if (vec == 4 && make_rows_args(plan, &rows))
+        return lp::launch_kernel(reinterpret_cast<const void *>(&partition_rows_kernel), dim3((rows.rows + rows.R - 1) / rows.R),
+                                 dim3(kThreads), rows.R * rows.w4 * 16, st, reinterpret_cast<const float4 *>(z),
+                                 reinterpret_cast<float4 *>(subs_packed), rows);
+    switch (vec) {
         case 4: return launch_partition<4>(plan, z, subs_packed, st);
         case 2: return launch_partition<2>(plan, z, subs_packed, st);
         default: return launch_partition<1>(plan, z, subs_packed, st);
