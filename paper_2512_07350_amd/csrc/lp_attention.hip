@@ -23,9 +23,14 @@
 //  * Q is multiplied by scale*log2(e) once and re-rounded to bf16, and the score
 //    accumulators start at -m (m = running maximum, log2 units), so a probability
 //    is a bare exp2 of the accumulator.
-//  * The running maximum is only raised when some score exceeds it by more than
-//    kRescaleThreshold; probabilities then stay below 2^kRescaleThreshold and the
-//    output accumulators are rescaled in a rarely taken, wave-uniform branch.
+//  * A segment's rounds run first with the maximum fixed at what the segment's first round made
+//    it and no look at the scores at all: exp2 of a score 100 log2 units above that maximum is
+//    still an ordinary binary32 / bf16 number, and numerator and denominator of the final
+//    division carry the same power of two.  Only if a row sum or an accumulator comes out
+//    non-finite (a score about 2^7 log2 units above the first round's) does the workgroup run
+//    the segment again, this time raising the maximum lazily: when some score exceeds it by
+//    more than kRescaleThreshold, in a rarely taken, wave-uniform branch that rescales the
+//    output accumulators.
 //  * The score product of round r+1, the softmax of round r and the PV product of round
 //    r-1 share one step, and the step's vector and LDS work is cut into one small window
 //    per matrix instruction (pipeline_step), so that the one wavefront of a SIMD has its
@@ -450,7 +455,7 @@ __device__ __forceinline__ uint32_t next_stage(uint32_t off) {
 // the products issued for rounds that do not exist add nothing; their operands are read
 // from valid, if stale, LDS addresses.  MASK = false is for steps whose rounds i+1 lie
 // wholly inside the segment and keeps the step free of conditionals.
-template <int D, int NB, int SUB, bool MASK>
+template <int D, int NB, int SUB, bool MASK, bool CHECK>
 __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &c, int i, bool first,
                                               Pipe<D, NB> &w, f32x16 (&s_cur)[NB], f32x16 (&s_nxt)[NB],
                                               bf16x8 (&p_prev)[NB][2], bf16x8 (&p_cur)[NB][2]) {
@@ -555,7 +560,7 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
             settle_scores<NB>(s_nxt, false);
             if (MASK) mask_scores<NB>(i + 1, c.half, c.key_end, s_nxt);
         }
-        if constexpr (m >= kMaxFrom) {
+        if constexpr (CHECK && m >= kMaxFrom) {
             constexpr int wdx = m - kMaxFrom, nbm = wdx % NB, first = (16 * (wdx / NB)) / kMaxWin;
             // three-operand maxima, written out so that no operand is first passed through a
             // quieting v_max (the scores come from assembly statements, so the compiler cannot
@@ -574,7 +579,7 @@ __device__ __forceinline__ void pipeline_step(uint32_t lds0, const Lane<D, NB> &
     // what the last two windows left to convert and to add
     vector_tail<NB, NB * 8, (M - 1) * X / 2, (M - 2) * X / 2>(ex, pw, p_cur, w.l_run);
     vector_tail<NB, NB * 8, NB * 8, (M - 1) * X / 2>(ex, pw, p_cur, w.l_run);
-    raise_maximum<D, NB>(lane_max, s_nxt, w.neg_m, p_cur, w.acc, w.l_run);
+    if constexpr (CHECK) raise_maximum<D, NB>(lane_max, s_nxt, w.neg_m, p_cur, w.acc, w.l_run);
 }
 
 // Launch parameters.  A unit is one 256-row query tile of one head; every unit walks
@@ -791,6 +796,23 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                                        __uint_as_float(u[e] & 0xffff0000u) * a.scale_log2e);
                 w.qreg[nb][kk] = t.v;
             }
+        // the Q^T operands now live in AGPRs for the whole segment (left to itself the register
+        // allocator may keep them elsewhere and copy each into one shared AGPR quad right before
+        // its product, overwriting the quad the product issued just before is still reading)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+a"(w.qreg[nb][kk]));
+
+        // ---- the segment's rounds.  Run first without the running-maximum check (CHECK = false):
+        // the maximum stays what the first round made it, a probability is exp2 of whatever the
+        // score is above that, and as long as nothing overflows binary32 / bf16 (2^127) the result
+        // is the same sum of the same terms, only scaled by another power of two on both sides of
+        // the final division.  If a row sum or an accumulator does come out non-finite -- some
+        // score exceeded the first round's maximum by about 2^7 in log2 units -- the workgroup
+        // runs the segment again with the check (CHECK = true), which raises the maximum as it goes.
+        auto run_segment = [&](auto checked_c) {
+        constexpr bool CHECK = decltype(checked_c)::value;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -799,13 +821,6 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
                 for (int r = 0; r < 16; ++r) w.acc[mb][nb][r] = 0.0f;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) w.l_run[nb] = 0.0f;
-        // the Q^T operands now live in AGPRs for the whole segment (left to itself the register
-        // allocator may keep them elsewhere and copy each into one shared AGPR quad right before
-        // its product, overwriting the quad the product issued just before is still reading)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) asm volatile("" : "+a"(w.qreg[nb][kk]));
         settle_acc<D, NB>(w.acc, true);
 
         // ---- LDS operand addresses in stage 0 (recomputed from an opaque copy of the lane
@@ -872,12 +887,33 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
         // the last round (and a step past it, if the count is odd, adds nothing)
         int i = i_begin;
         for (; (i + 3) * 32 <= c.key_end; i += 2) {      // rounds i+1 and i+2 are whole
-            pipeline_step<D, NB, 0, false>(lds0, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
-            pipeline_step<D, NB, 1, false>(lds0, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+            pipeline_step<D, NB, 0, false, CHECK>(lds0, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1, false, CHECK>(lds0, c, i + 1, false, w, s_b, s_a, p_a, p_b);
         }
         for (; i <= i_end; i += 2) {
-            pipeline_step<D, NB, 0, true>(lds0, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
-            pipeline_step<D, NB, 1, true>(lds0, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+            pipeline_step<D, NB, 0, true, CHECK>(lds0, c, i, i == i_begin, w, s_a, s_b, p_b, p_a);
+            pipeline_step<D, NB, 1, true, CHECK>(lds0, c, i + 1, false, w, s_b, s_a, p_a, p_b);
+        }
+        };   // run_segment
+
+        run_segment(std::false_type{});
+        {
+            // anything not finite in this lane's row sums or accumulators?  (x - x is 0 for every finite x)
+            settle_acc<D, NB>(w.acc, false);
+            float probe = 0.0f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                probe += w.l_run[nb] - w.l_run[nb];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) probe += w.acc[mb][nb][r] - w.acc[mb][nb][r];
+            }
+            // the barrier also makes sure that every wave has left the segment's tiles
+            if (__syncthreads_or(!(probe == 0.0f))) {
+                start_tiles<D, NB>(lds0, a, seg, c, w, n, stride_tok);
+                run_segment(std::true_type{});
+            }
         }
 
         // ---- the next segment's first tiles set out before this segment's results are

@@ -277,3 +277,33 @@ def test_scores_that_keep_rising_along_the_keys(balanced):
     # and the same keys in reverse order (the first round already holds the maximum)
     got_r = g.hip_attention(q, k[::-1].copy(), v[::-1].copy(), balanced=balanced)
     g.assert_attention_close(got_r, want, "falling scores")
+
+
+@pytest.mark.parametrize("balanced", [True, False], ids=["balanced", "tile-per-workgroup"])
+@pytest.mark.parametrize("hd", [64, 128])
+@pytest.mark.parametrize("profile", ["ramp", "cliff"])
+def test_scores_far_above_the_first_round(balanced, hd, profile):
+    """Scores that climb 8 log2 units per 32-key round up to 2^256 times the first round's level
+    and stay there ("ramp"), or get there in one step ("cliff"): exp2 of a score relative to the first round's maximum overflows
+    binary32, which the kernel has to notice and recover from (it repeats the segment with the
+    running-maximum check).  Every operand is exactly representable, the scale is chosen so that
+    the pre-scaled queries are too, so the stated tolerance applies unchanged."""
+    from tests import gpu_util as g
+    n, heads = 1500, 2
+    rng = np.random.default_rng(1234)
+    base = np.where(rng.random((heads, hd)) < 0.5, -1.0, 1.0).astype(np.float32)       # q . k = hd * (q level) * (k level)
+    if profile == "ramp":
+        level = np.minimum(np.floor(np.arange(n) / 32.0), 32.0).astype(np.float32)      # 0, 1, ..., 32, 32, ...
+    else:                                            # one step of 2^256 inside the second round: also met by a
+        level = np.where(np.arange(n) < 40, 0.0, 32.0).astype(np.float32)   # workgroup that holds only the first tiles
+    qf = np.broadcast_to(base[None] * np.float32(64.0 / hd), (n, heads, hd)).copy()
+    kf = base[None] * level[:, None, None]
+    vf = rng.standard_normal((n, heads, hd)).astype(np.float32)
+    q, k, v = (synth.f32_to_bf16_bits(a) for a in (qf, kf, vf))
+    scale = 0.125 / np.log2(np.e)                    # scores in log2 units: 64 * level * 0.125 = 8 * level
+    got = g.hip_attention(q, k, v, scale=scale, balanced=balanced)
+    want = orc.attention(q, k, v, scale=scale)
+    g.assert_attention_close(got, want, "scores far above the first round")
+    plateau = synth.bf16_bits_to_f32(v)[level == 32.0].mean(axis=0)
+    assert np.max(np.abs(want[700] - plateau)) < 1e-2          # the oracle itself: the plateau's keys carry the weight
+

@@ -23,6 +23,9 @@ CASES = [
     ((16, 21, 60, 104), P122, 2, 2, (0, 1, 2)),          # 81-frame 480p on 2 devices
     ((16, 21, 60, 104), P122, 8, 2, (0, 1, 2)),          # ... on 8 (along T: last core past the end)
     ((2, 3, 4, 40), P122, 8, 2, (2,)),                   # a core wholly past the end: front ramp longer than the partition
+    ((3, 5, 7, 40), (1, 1, 4), 4, 1, (2,)),              # split along W by rows through LDS: 105 rows, the last workgroup takes 9
+    ((2, 2, 3, 8208), (1, 1, 4), 3, 2, (2,)),            # a row of 32832 bytes: too long for the row kernel's LDS share
+    ((1, 1, 70, 24), (1, 1, 4), 2, 1, (2,)),             # rows of 24 floats, sub-latent rows of 16
 ]
 
 
