@@ -898,16 +898,21 @@ __global__ __launch_bounds__(waves_of(NB) * 64) void attention_kernel(const Attn
 
         run_segment(std::false_type{});
         {
-            // anything not finite in this lane's row sums or accumulators?  (x - x is 0 for every finite x)
+            // anything in this lane's row sums or accumulators that is not finite, or within 2^7 of
+            // not being so (partial rows are stored as bf16)?  y - y is 0 for every finite y
             settle_acc<D, NB>(w.acc, false);
             float probe = 0.0f;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                probe += w.l_run[nb] - w.l_run[nb];
+                const float yl = w.l_run[nb] * 128.0f;
+                probe += yl - yl;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) probe += w.acc[mb][nb][r] - w.acc[mb][nb][r];
+                    for (int r = 0; r < 16; ++r) {
+                        const float y = w.acc[mb][nb][r] * 128.0f;
+                        probe += y - y;
+                    }
             }
             // the barrier also makes sure that every wave has left the segment's tiles
             if (__syncthreads_or(!(probe == 0.0f))) {

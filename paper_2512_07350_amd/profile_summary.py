@@ -23,7 +23,8 @@ import os
 import re
 import sys
 
-OURS = ("attention_kernel", "combine_kernel", "partition_kernel", "reconstruct_kernel", "gemm_kernel", "norm_rope_kernel")
+OURS = ("attention_kernel", "combine_kernel", "partition_kernel", "partition_rows_kernel", "reconstruct_kernel", "gemm_kernel",
+        "norm_rope_kernel")
 COPY_KIB = 256 * 1024          # bench.py --copy-calibration copies 256 MiB
 
 
