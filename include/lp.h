@@ -192,6 +192,11 @@ int lp_reconstruct_guided_step_partition(const lp_plan *plan, const float *cond_
  * scale*log2(e) and re-rounded to bf16 once; the softmax is binary32;
  * probabilities are rounded to bf16 before the second product and the result is
  * rounded to bf16 on store.
+ * Scores of any finite size are handled.  A workgroup first takes its stretch of
+ * keys relative to the largest score among its first 32; if some later score
+ * lies so far above that one (about 2^7 in log2 units) that a probability, a row
+ * sum or an output accumulator overflows binary32, it takes the stretch again
+ * with a running maximum.  Such inputs cost up to twice the time, not accuracy.
  * Inputs must be finite.  With an infinity or a NaN in q, k or v the affected
  * output rows are unspecified (typically NaN, also where the definition would
  * give an infinity: rows of v beyond a probability of exactly 0 are still
