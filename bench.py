@@ -381,6 +381,7 @@ def other_configs(ctx, args):
             entry["loop"] = m["loop"]
         if cfg == 2:
             entry["K1_full_sequence"] = k1_comparison(ctx, run)
+            entry["block_ops"] = block_ops(ctx, run, check=False)      # the 12-head block: d_model 1536
         out.append(entry)
         del run
         torch.cuda.empty_cache()
