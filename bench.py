@@ -344,7 +344,7 @@ def rate(nbytes, ms, steps):
 def attention_rows_per_wave():
     """Query rows one wavefront of attention_kernel owns (read from the kernel source, for the label only)."""
     import re
-    m = re.search(r"constexpr int blocks_per_wave\(int d\) \{ return (\d+); \}", open(ATTENTION_SOURCE).read())
+    m = re.search(r"constexpr int blocks_per_wave\([^)]*\) \{ return (\d+); \}", open(ATTENTION_SOURCE).read())
     return 32 * int(m.group(1)) if m else 32
 
 

@@ -80,7 +80,7 @@ constexpr int kBM = 256;                      // query rows per workgroup
 // A wavefront owns NB blocks of 32 query rows; the workgroup has kBM / (32 NB) wavefronts.
 constexpr int waves_of(int nb) { return kBM / (32 * nb); }
 // NB used by lp_attention: 64 query rows per wavefront (one wavefront per SIMD, four per workgroup)
-constexpr int blocks_per_wave(int d) { return 2; }
+constexpr int blocks_per_wave(int /* head_dim */) { return 2; }
 constexpr int kBN = 64;                       // keys per LDS tile (two rounds of 32)
 constexpr int kStages = 4;                    // LDS stages: three tiles in use plus one arriving
 constexpr float kRescaleThreshold = 8.0f;     // log2 units the running max may lag behind
@@ -256,7 +256,6 @@ __device__ __forceinline__ void mfma_pv(f32x16 &acc, const bf16x8 &vt, const bf1
 // keep their program order among themselves, so whatever produces x comes before this point
 // and whatever uses x afterwards comes after it; no instruction is emitted.
 __device__ __forceinline__ void pin(float &x) { asm volatile("" : "+v"(x)); }
-__device__ __forceinline__ void pin(f32x2 &x) { asm volatile("" : "+v"(x)); }
 __device__ __forceinline__ void pin(uint32_t &x) { asm volatile("" : "+v"(x)); }
 
 // Scores written by matrix instructions become readable by vector instructions: 16 wait
@@ -280,13 +279,6 @@ __device__ __forceinline__ void settle_acc(f32x16 (&acc)[D / 32][NB], bool after
     for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) asm volatile("" : "+a"(acc[mb][nb]));
-}
-
-// Two scores (already relative to the running maximum) -> one packed pair of bf16 probabilities.
-__device__ __forceinline__ uint32_t probability_pair(const f32x2 &s) {
-    union { bf16x2 p; uint32_t u; } w;
-    w.p = to_bf16x2(__builtin_amdgcn_exp2f(s[0]), __builtin_amdgcn_exp2f(s[1]));
-    return w.u;
 }
 
 // The row sum adds the rounded probabilities.
