@@ -119,8 +119,8 @@ __device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rsrc, uint
 __device__ __forceinline__ void wait_all_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Workgroup ids are dealt round robin to the 8 XCDs; remap so that each XCD owns a contiguous
-// stretch of tiles (the feature tiles of one token tile, then the next token tile) and the x
-// tile of a token tile stays in one XCD's L2.
+// stretch of the tile order (see the panels in gemm_kernel) and what neighbouring tiles share
+// stays in one XCD's L2.
 __device__ __forceinline__ uint32_t logical_workgroup(uint32_t b, uint32_t n_wg) {
     const uint32_t xcd = b % 8, slot = b / 8;
     const uint32_t base = n_wg / 8, rem = n_wg % 8;
